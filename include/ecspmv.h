@@ -1,0 +1,152 @@
+/*
+ * ecspmv.h -- C ABI of the MI355X-native batch-1 SpMV  y = W x  over EC-CSR.
+ *
+ * EC-CSR (paper, Section 6) stores a pruned FP16 weight matrix as dense g-grained blocks
+ * found by hierarchical block extraction (Section 4, Algorithms 1 and 2) plus the
+ * residual 1-grained rows, with 8-bit delta-encoded column indices (Section 6.2).
+ * ecspmv_build_* runs the offline phase on the host (Sections 4, 5, 6); ecspmv_run is the
+ * online phase (Section 7): one HIP kernel launch on a caller-supplied stream.
+ *
+ * Conventions
+ *  - Every function returns an int status: ECSPMV_OK (0) or a negative ECSPMV_ERR_* code.
+ *    Nothing throws, aborts or prints.  Output arguments are untouched on error.
+ *  - "host" / "device" in an argument's comment says which memory the pointer addresses.
+ *  - FP16 data crosses the ABI as uint16_t IEEE 754 binary16 bit patterns.
+ *  - A matrix entry is stored iff its bits are neither +0 nor -0 (bits & 0x7FFF != 0).
+ *  - The handle owns host memory only.  The caller owns W, x, y and the device buffers and
+ *    must keep a device image alive and unchanged while runs on it are in flight.
+ *  - Streams are passed as void* (a hipStream_t; NULL = the default stream).
+ *  - ecspmv_build_* may be called from several threads at once; a handle is read-only after
+ *    ecspmv_upload and may then be used from several threads / streams, provided the runs
+ *    write different y.
+ */
+#ifndef ECSPMV_H
+#define ECSPMV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ECSPMV_OK                 0
+#define ECSPMV_ERR_INVALID       -1  /* NULL pointer, bad size, ld < n, unsorted / duplicate / out-of-range CSR column */
+#define ECSPMV_ERR_UNSUPPORTED   -2  /* n > 65535, delta_bits != 8, max_granularity not in {1,2,4,8,16}, too many rows */
+#define ECSPMV_ERR_NOMEM         -3  /* host allocation failed */
+#define ECSPMV_ERR_HIP           -4  /* a HIP call failed; ecspmv_last_hip_error() has its code */
+#define ECSPMV_ERR_NOT_UPLOADED  -5  /* ecspmv_run before ecspmv_upload */
+#define ECSPMV_ERR_TOO_SMALL     -6  /* caller's buffer is smaller than required */
+
+typedef struct ecspmv_matrix ecspmv_matrix;     /* opaque: the host-side EC-CSR image of one matrix */
+typedef struct ecspmv_csr ecspmv_csr;           /* opaque: plain CSR (comparison kernel) */
+
+/* Options of the offline phase.  NULL, or a zeroed struct with struct_size set, gives the
+ * defaults.  Fields beyond struct_size are taken as 0 (= default). */
+typedef struct ecspmv_build_opts {
+    uint32_t struct_size;     /* sizeof(ecspmv_build_opts) as the caller compiled it */
+    int32_t  delta_bits;      /* width of a delta index (Section 6.2, range R_P = 2^bits); 0 = 8; only 8 is built */
+    int32_t  max_granularity; /* largest block granularity g (rows per block, Section 4); 0 = 8; 1 = no extraction */
+    int32_t  max_rounds;      /* cap on extraction rounds per level (Algorithm 1, inner loop); 0 = 64 */
+    int32_t  num_panels;      /* row panels = workgroups of the SpMV launch; 0 = auto (256, fewer for small m) */
+    int32_t  num_threads;     /* host threads for the offline phase; 0 = hardware concurrency, at most 16 */
+    int32_t  threads_per_wg;  /* workgroup size of the SpMV launch, multiple of 64 in [64,1024]; 0 = 1024 */
+    uint64_t flags;           /* ECSPMV_FLAG_* */
+} ecspmv_build_opts;
+
+#define ECSPMV_FLAG_GLOBAL_MATCHING  1ull /* one panel for extraction: row matching over all rows as in Algorithm 2
+                                             (the launch then has a single workgroup: for studies on small inputs) */
+#define ECSPMV_FLAG_NO_REORDER       2ull /* keep blocks in extraction order instead of longest-first (Section 5) */
+
+/* What ecspmv_stats reports (Section 8.2 storage study, Table 2 padding). */
+typedef struct ecspmv_stats_t {
+    uint32_t struct_size;
+    int64_t  m, n, nnz;                /* stored entries of W */
+    int64_t  image_bytes;              /* whole device image */
+    int64_t  value_bytes;              /* FP16 values incl. padding */
+    int64_t  delta_bytes;              /* 8-bit delta indices incl. padding */
+    int64_t  meta_bytes;               /* headers, bases, row/slot tables */
+    int64_t  slack_bytes;              /* alignment gaps and per-panel slack up to the common panel stride */
+    int64_t  csr32_bytes;              /* 6*nnz + 4*(m+1): int32 columns + FP16 values + int32 row pointers */
+    int64_t  csr16_bytes;              /* 4*nnz + 4*(m+1) */
+    int64_t  nnz_by_g[5];              /* stored entries held at granularity 1, 2, 4, 8, 16 */
+    int64_t  units_by_g[5];            /* [0] = residual lane units (16 elements), [t>=1] = 64-column units of g = 2^t */
+    int64_t  pad_elements;             /* explicit zeros: gap fillers + row-tail alignment (residual rows only) */
+    int64_t  gap_pad_elements;         /* of those, zeros inserted because a column gap exceeded 255 */
+    int32_t  num_panels, threads_per_wg;
+    int64_t  panel_stride, meta_stride, lds_bytes;
+    int64_t  max_panel_bytes, min_panel_bytes;
+    double   x_access_cost;            /* sum over stored entries of 1/g(e): the paper's x-access objective with L = 1 */
+    double   build_seconds;
+    int64_t  delta_hist[9];            /* residual deltas: 0, 1, 2-3, 4-7, ..., 64-127, 128-255 */
+} ecspmv_stats_t;
+
+/* ---- offline phase (host) -------------------------------------------------------------------------- */
+
+/* Build from a dense row-major FP16 matrix.  W: host, m rows of n entries, row stride ld >= n (elements).
+ * Caller keeps W.  *out receives a new handle (free with ecspmv_destroy).  m, n >= 1; n <= 65535. */
+int ecspmv_build_dense(const uint16_t *W, int64_t m, int64_t n, int64_t ld,
+                       const ecspmv_build_opts *opts, ecspmv_matrix **out);
+
+/* Build from CSR.  rowptr: host, m+1 entries, rowptr[0] = 0, non-decreasing; col: host, strictly increasing
+ * within a row, in [0, n); val: host FP16 bits (entries equal to +-0 are dropped). */
+int ecspmv_build_csr(const int64_t *rowptr, const int32_t *col, const uint16_t *val,
+                     int64_t m, int64_t n, const ecspmv_build_opts *opts, ecspmv_matrix **out);
+
+void ecspmv_destroy(ecspmv_matrix *A);          /* NULL is a no-op */
+
+/* Fill *st (st->struct_size must be set by the caller). */
+int ecspmv_stats(const ecspmv_matrix *A, ecspmv_stats_t *st);
+
+/* Decode the image back to coordinate triples by walking it the way the kernel does, dropping padding.
+ * Call with rows = cols = vals = NULL to get *nnz; then with host arrays of *nnz entries each (capacity
+ * passed in *nnz).  Output order is image order (not sorted). */
+int ecspmv_decode(const ecspmv_matrix *A, int64_t *nnz, int32_t *rows, int32_t *cols, uint16_t *vals);
+
+/* The block sets (Algorithm 1's output): for every extracted unit, its granularity, its g original rows and
+ * its 64 columns.  Call with NULLs to get the counts (*n_units, *n_rows = sum of g over units).
+ * g: n_units entries; unit_rows: concatenated row lists; unit_cols: 64 entries per unit.  Host arrays. */
+int ecspmv_block_sets(const ecspmv_matrix *A, int64_t *n_units, int64_t *n_rows,
+                      int32_t *g, int32_t *unit_rows, int32_t *unit_cols);
+
+/* ---- device image ---------------------------------------------------------------------------------- */
+
+/* Size of the device image in bytes (a multiple of 256). */
+int ecspmv_device_bytes(const ecspmv_matrix *A, size_t *bytes);
+
+/* Copy the image into d_buf (device, 256-byte aligned, >= ecspmv_device_bytes, allocated and owned by the
+ * caller) on `stream`, and remember d_buf in the handle.  Returns after the copy has completed. */
+int ecspmv_upload(ecspmv_matrix *A, void *d_buf, size_t bytes, void *stream);
+
+/* ---- online phase ---------------------------------------------------------------------------------- */
+
+/* y = W x (overwrites y; every one of the m entries is written).  d_x: device, n FP16, 2-byte aligned
+ * (16-byte alignment takes the faster staging path).  d_y: device, m FP16.  x and y must not overlap.
+ * Asynchronous on `stream`: exactly one kernel launch, no allocation, no memset, no host synchronisation.
+ * x must be finite: padding zeros are multiplied with x entries. */
+int ecspmv_run(const ecspmv_matrix *A, const void *d_x, void *d_y, void *stream);
+
+/* ---- comparison: plain CSR (int32 column index + FP16 value per entry, one wavefront per row) ------- */
+
+int ecspmv_csr_build_dense(const uint16_t *W, int64_t m, int64_t n, int64_t ld, ecspmv_csr **out);
+void ecspmv_csr_destroy(ecspmv_csr *C);
+int ecspmv_csr_device_bytes(const ecspmv_csr *C, size_t *bytes);
+int ecspmv_csr_upload(ecspmv_csr *C, void *d_buf, size_t bytes, void *stream);
+int ecspmv_csr_run(const ecspmv_csr *C, const void *d_x, void *d_y, void *stream);
+
+/* ---- measurement aid: streaming-read ceiling -------------------------------------------------------- */
+
+/* Reads `bytes` (multiple of 16) from d_buf (device, 16-byte aligned) with 128-bit loads from `num_wg`
+ * workgroups of 1024 threads and writes one 32-bit checksum per workgroup to d_out (device, num_wg words).
+ * One launch, asynchronous on `stream`. */
+int ecspmv_stream_read(const void *d_buf, size_t bytes, void *d_out, int32_t num_wg, void *stream);
+
+/* ---- errors ---------------------------------------------------------------------------------------- */
+
+const char *ecspmv_strerror(int status);
+int ecspmv_last_hip_error(void);                /* hipError_t of the most recent failed HIP call on this thread */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ECSPMV_H */

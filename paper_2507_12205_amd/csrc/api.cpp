@@ -1,0 +1,298 @@
+// C ABI of the library (see include/ecspmv.h): argument checks, option defaults, handle bookkeeping.
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "../../include/ecspmv.h"
+#include "encoder.h"
+#include "launch.h"
+
+struct ecspmv_matrix {
+    ecs::Image image;
+    void *d_image = nullptr;
+};
+
+struct ecspmv_csr {
+    int64_t m = 0, n = 0, nnz = 0;
+    std::vector<int32_t> rowptr, col;
+    std::vector<uint16_t> val;
+    size_t off_col = 0, off_val = 0, bytes = 0;
+    uint8_t *d_buf = nullptr;
+};
+
+namespace {
+
+thread_local int g_last_hip_error = 0;
+
+int hip_status(int e)
+{
+    if (e == 0) return ECSPMV_OK;
+    g_last_hip_error = e;
+    return ECSPMV_ERR_HIP;
+}
+
+int map_build_error(int e)
+{
+    if (e == 0) return ECSPMV_OK;
+    if (e == -2) return ECSPMV_ERR_UNSUPPORTED;
+    return ECSPMV_ERR_INVALID;
+}
+
+int parse_opts(const ecspmv_build_opts *o, ecs::BuildParams &bp)
+{
+    ecspmv_build_opts opts;
+    std::memset(&opts, 0, sizeof(opts));
+    if (o) {
+        if (o->struct_size < sizeof(uint32_t)) return ECSPMV_ERR_INVALID;
+        std::memcpy(&opts, o, o->struct_size < sizeof(opts) ? o->struct_size : sizeof(opts));
+    }
+    if (opts.delta_bits != 0 && opts.delta_bits != 8) return ECSPMV_ERR_UNSUPPORTED;
+    const int g = opts.max_granularity ? opts.max_granularity : 8;
+    if (g != 1 && g != 2 && g != 4 && g != 8 && g != 16) return ECSPMV_ERR_UNSUPPORTED;
+    bp.max_granularity = g;
+    if (opts.max_rounds < 0 || opts.num_panels < 0 || opts.num_threads < 0) return ECSPMV_ERR_INVALID;
+    bp.max_rounds = opts.max_rounds ? opts.max_rounds : 64;
+    bp.num_panels = opts.num_panels;
+    bp.num_threads = opts.num_threads;
+    const int t = opts.threads_per_wg ? opts.threads_per_wg : 1024;
+    if (t < 64 || t > 1024 || t % 64) return ECSPMV_ERR_INVALID;
+    bp.threads_per_wg = t;
+    bp.global_matching = (opts.flags & ECSPMV_FLAG_GLOBAL_MATCHING) != 0;
+    bp.reorder = (opts.flags & ECSPMV_FLAG_NO_REORDER) == 0;
+    return ECSPMV_OK;
+}
+
+int finish_build(const ecs::Csr &A, const ecs::BuildParams &bp, ecspmv_matrix **out)
+{
+    ecspmv_matrix *h = new (std::nothrow) ecspmv_matrix;
+    if (!h) return ECSPMV_ERR_NOMEM;
+    int e = ecs::build_image(A, bp, h->image);
+    if (e) {
+        delete h;
+        return map_build_error(e);
+    }
+    if (h->image.lds_bytes > 160u * 1024u) {
+        delete h;
+        return ECSPMV_ERR_UNSUPPORTED;
+    }
+    *out = h;
+    return ECSPMV_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int ecspmv_build_dense(const uint16_t *W, int64_t m, int64_t n, int64_t ld, const ecspmv_build_opts *opts,
+                       ecspmv_matrix **out)
+{
+    if (!W || !out || m <= 0 || n <= 0 || ld < n) return ECSPMV_ERR_INVALID;
+    if (n > 65535 || m > 0x7fffffff) return ECSPMV_ERR_UNSUPPORTED;
+    ecs::BuildParams bp;
+    int s = parse_opts(opts, bp);
+    if (s) return s;
+    try {
+        ecs::Csr A;
+        ecs::csr_from_dense(W, m, n, ld, bp.num_threads, A);
+        return finish_build(A, bp, out);
+    } catch (const std::bad_alloc &) {
+        return ECSPMV_ERR_NOMEM;
+    }
+}
+
+int ecspmv_build_csr(const int64_t *rowptr, const int32_t *col, const uint16_t *val, int64_t m, int64_t n,
+                     const ecspmv_build_opts *opts, ecspmv_matrix **out)
+{
+    if (!rowptr || !out || m <= 0 || n <= 0) return ECSPMV_ERR_INVALID;
+    if (rowptr[m] < 0 || (rowptr[m] > 0 && (!col || !val))) return ECSPMV_ERR_INVALID;
+    if (n > 65535 || m > 0x7fffffff) return ECSPMV_ERR_UNSUPPORTED;
+    ecs::BuildParams bp;
+    int s = parse_opts(opts, bp);
+    if (s) return s;
+    try {
+        ecs::Csr A;
+        if (ecs::csr_from_csr(rowptr, col, val, m, n, A)) return ECSPMV_ERR_INVALID;
+        return finish_build(A, bp, out);
+    } catch (const std::bad_alloc &) {
+        return ECSPMV_ERR_NOMEM;
+    }
+}
+
+void ecspmv_destroy(ecspmv_matrix *A) { delete A; }
+
+int ecspmv_stats(const ecspmv_matrix *A, ecspmv_stats_t *st)
+{
+    if (!A || !st || st->struct_size < sizeof(uint32_t)) return ECSPMV_ERR_INVALID;
+    const uint32_t want = st->struct_size < sizeof(ecspmv_stats_t) ? st->struct_size : (uint32_t)sizeof(ecspmv_stats_t);
+    ecspmv_stats_t tmp = A->image.stats;
+    tmp.struct_size = want;
+    std::memcpy(st, &tmp, want);
+    return ECSPMV_OK;
+}
+
+int ecspmv_decode(const ecspmv_matrix *A, int64_t *nnz, int32_t *rows, int32_t *cols, uint16_t *vals)
+{
+    if (!A || !nnz) return ECSPMV_ERR_INVALID;
+    try {
+        ecs::Triples t;
+        if (ecs::walk_image(A->image, &t, nullptr)) return ECSPMV_ERR_INVALID;
+        const int64_t count = (int64_t)t.rows.size();
+        if (!rows && !cols && !vals) {
+            *nnz = count;
+            return ECSPMV_OK;
+        }
+        if (!rows || !cols || !vals) return ECSPMV_ERR_INVALID;
+        if (*nnz < count) return ECSPMV_ERR_TOO_SMALL;
+        if (count) {
+            std::memcpy(rows, t.rows.data(), sizeof(int32_t) * (size_t)count);
+            std::memcpy(cols, t.cols.data(), sizeof(int32_t) * (size_t)count);
+            std::memcpy(vals, t.vals.data(), sizeof(uint16_t) * (size_t)count);
+        }
+        *nnz = count;
+        return ECSPMV_OK;
+    } catch (const std::bad_alloc &) {
+        return ECSPMV_ERR_NOMEM;
+    }
+}
+
+int ecspmv_block_sets(const ecspmv_matrix *A, int64_t *n_units, int64_t *n_rows, int32_t *g, int32_t *unit_rows,
+                      int32_t *unit_cols)
+{
+    if (!A || !n_units || !n_rows) return ECSPMV_ERR_INVALID;
+    try {
+        ecs::BlockSets b;
+        if (ecs::walk_image(A->image, nullptr, &b)) return ECSPMV_ERR_INVALID;
+        const int64_t nu = (int64_t)b.g.size(), nr = (int64_t)b.rows.size();
+        if (!g && !unit_rows && !unit_cols) {
+            *n_units = nu;
+            *n_rows = nr;
+            return ECSPMV_OK;
+        }
+        if (!g || !unit_rows || !unit_cols) return ECSPMV_ERR_INVALID;
+        if (*n_units < nu || *n_rows < nr) return ECSPMV_ERR_TOO_SMALL;
+        if (nu) {
+            std::memcpy(g, b.g.data(), sizeof(int32_t) * (size_t)nu);
+            std::memcpy(unit_rows, b.rows.data(), sizeof(int32_t) * (size_t)nr);
+            std::memcpy(unit_cols, b.cols.data(), sizeof(int32_t) * (size_t)nu * ECS_UNIT_COLS);
+        }
+        *n_units = nu;
+        *n_rows = nr;
+        return ECSPMV_OK;
+    } catch (const std::bad_alloc &) {
+        return ECSPMV_ERR_NOMEM;
+    }
+}
+
+int ecspmv_device_bytes(const ecspmv_matrix *A, size_t *bytes)
+{
+    if (!A || !bytes) return ECSPMV_ERR_INVALID;
+    *bytes = A->image.bytes.size();
+    return ECSPMV_OK;
+}
+
+int ecspmv_upload(ecspmv_matrix *A, void *d_buf, size_t bytes, void *stream)
+{
+    if (!A || !d_buf || (reinterpret_cast<uintptr_t>(d_buf) & 255)) return ECSPMV_ERR_INVALID;
+    if (bytes < A->image.bytes.size()) return ECSPMV_ERR_TOO_SMALL;
+    int lim = 0;
+    int e = ecs::device_lds_limit(&lim);
+    if (e) return hip_status(e);
+    if ((int64_t)A->image.lds_bytes > (int64_t)lim) return ECSPMV_ERR_UNSUPPORTED;
+    e = ecs::copy_to_device(d_buf, A->image.bytes.data(), A->image.bytes.size(), stream);
+    if (e) return hip_status(e);
+    A->d_image = d_buf;
+    return ECSPMV_OK;
+}
+
+int ecspmv_run(const ecspmv_matrix *A, const void *d_x, void *d_y, void *stream)
+{
+    if (!A || !d_x || !d_y) return ECSPMV_ERR_INVALID;
+    if ((reinterpret_cast<uintptr_t>(d_x) & 1) || (reinterpret_cast<uintptr_t>(d_y) & 1)) return ECSPMV_ERR_INVALID;
+    if (!A->d_image) return ECSPMV_ERR_NOT_UPLOADED;
+    const ecs::Image &im = A->image;
+    return hip_status(ecs::launch_ecspmv(A->d_image, d_x, d_y, (uint32_t)im.n, (uint32_t)im.num_panels,
+                                         (uint32_t)im.threads_per_wg, im.panel_stride, im.meta_stride, im.lds_bytes,
+                                         stream));
+}
+
+int ecspmv_csr_build_dense(const uint16_t *W, int64_t m, int64_t n, int64_t ld, ecspmv_csr **out)
+{
+    if (!W || !out || m <= 0 || n <= 0 || ld < n) return ECSPMV_ERR_INVALID;
+    try {
+        ecs::Csr A;
+        ecs::csr_from_dense(W, m, n, ld, 0, A);
+        if (A.rowptr[(size_t)m] > 0x7fffffff || m > 0x7ffffffe) return ECSPMV_ERR_UNSUPPORTED;
+        ecspmv_csr *c = new (std::nothrow) ecspmv_csr;
+        if (!c) return ECSPMV_ERR_NOMEM;
+        c->m = m;
+        c->n = n;
+        c->nnz = A.rowptr[(size_t)m];
+        c->rowptr.resize((size_t)m + 1);
+        for (int64_t i = 0; i <= m; ++i) c->rowptr[(size_t)i] = (int32_t)A.rowptr[(size_t)i];
+        c->col.swap(A.col);
+        c->val.swap(A.val);
+        auto up = [](size_t v) { return (v + 255) / 256 * 256; };
+        c->off_col = up(4 * ((size_t)m + 1));
+        c->off_val = c->off_col + up(4 * (size_t)c->nnz);
+        c->bytes = c->off_val + up(2 * (size_t)c->nnz) + 256;
+        *out = c;
+        return ECSPMV_OK;
+    } catch (const std::bad_alloc &) {
+        return ECSPMV_ERR_NOMEM;
+    }
+}
+
+void ecspmv_csr_destroy(ecspmv_csr *C) { delete C; }
+
+int ecspmv_csr_device_bytes(const ecspmv_csr *C, size_t *bytes)
+{
+    if (!C || !bytes) return ECSPMV_ERR_INVALID;
+    *bytes = C->bytes;
+    return ECSPMV_OK;
+}
+
+int ecspmv_csr_upload(ecspmv_csr *C, void *d_buf, size_t bytes, void *stream)
+{
+    if (!C || !d_buf || (reinterpret_cast<uintptr_t>(d_buf) & 255)) return ECSPMV_ERR_INVALID;
+    if (bytes < C->bytes) return ECSPMV_ERR_TOO_SMALL;
+    uint8_t *d = static_cast<uint8_t *>(d_buf);
+    int e = ecs::copy_to_device(d, C->rowptr.data(), 4 * C->rowptr.size(), stream);
+    if (!e && C->nnz) e = ecs::copy_to_device(d + C->off_col, C->col.data(), 4 * C->col.size(), stream);
+    if (!e && C->nnz) e = ecs::copy_to_device(d + C->off_val, C->val.data(), 2 * C->val.size(), stream);
+    if (e) return hip_status(e);
+    C->d_buf = d;
+    return ECSPMV_OK;
+}
+
+int ecspmv_csr_run(const ecspmv_csr *C, const void *d_x, void *d_y, void *stream)
+{
+    if (!C || !d_x || !d_y) return ECSPMV_ERR_INVALID;
+    if (!C->d_buf) return ECSPMV_ERR_NOT_UPLOADED;
+    return hip_status(ecs::launch_csr(C->d_buf, C->d_buf + C->off_col, C->d_buf + C->off_val, d_x, d_y, (uint32_t)C->m,
+                                      stream));
+}
+
+int ecspmv_stream_read(const void *d_buf, size_t bytes, void *d_out, int32_t num_wg, void *stream)
+{
+    if (!d_buf || !d_out || num_wg <= 0 || (bytes & 15) || (reinterpret_cast<uintptr_t>(d_buf) & 15))
+        return ECSPMV_ERR_INVALID;
+    return hip_status(ecs::launch_stream_read(d_buf, bytes, d_out, (uint32_t)num_wg, stream));
+}
+
+const char *ecspmv_strerror(int status)
+{
+    switch (status) {
+    case ECSPMV_OK: return "ok";
+    case ECSPMV_ERR_INVALID: return "invalid argument";
+    case ECSPMV_ERR_UNSUPPORTED: return "unsupported size or option";
+    case ECSPMV_ERR_NOMEM: return "out of host memory";
+    case ECSPMV_ERR_HIP: return "HIP call failed (see ecspmv_last_hip_error)";
+    case ECSPMV_ERR_NOT_UPLOADED: return "matrix has no device image yet";
+    case ECSPMV_ERR_TOO_SMALL: return "buffer too small";
+    default: return "unknown status";
+    }
+}
+
+int ecspmv_last_hip_error(void) { return g_last_hip_error; }
+
+}  // extern "C"

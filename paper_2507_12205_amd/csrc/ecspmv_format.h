@@ -1,0 +1,75 @@
+// Device image layout of EC-CSR as this library stores it (shared by the host encoder and the HIP kernels).
+//
+// The paper's EC-CSR (Section 6.1) keeps, per block set, row_indices / block_indptr / base_indices /
+// delta_indices / block_values.  The same information is laid out here for 64-wide wavefronts and
+// 128-bit loads:
+//
+//   image  = [ImageHeader, 256 B] [panel 0] [panel 1] ... [panel P-1]        each panel `panel_stride` bytes
+//   panel  = [meta: PanelHeader + tables] [payload: deltas and values of each block set]
+//
+// A panel owns a contiguous range of output rows and is processed by one workgroup, so y needs no atomics.
+// Block sets inside a panel are kept apart by granularity (Section 6.1): g = 16, 8, 4, 2 and the 1-grained
+// residual.  The unit of a g >= 2 set is 64 block columns (16 lanes x 4 columns): one 16-bit base column,
+// 64 one-byte deltas (the first is 0, Section 6.2 worked example), 64*g FP16 values stored so that the k-th
+// 128-bit load of lane j (j = 0..15) sits at byte k*256 + j*16 of the unit (the permutation of Section
+// 6.3.2 for 16-byte vectors) and holds halfs [8k, 8k+8) of that lane's run values[(4j+c)*g + r].
+// The unit of the residual set is a "lane unit": 16 consecutive elements of one row (16 delta bytes, 16 FP16
+// values); 64 lane units form a chunk that one wavefront decodes with a prefix scan over lane totals.
+#ifndef ECSPMV_FORMAT_H
+#define ECSPMV_FORMAT_H
+
+#include <stdint.h>
+
+#define ECS_MAGIC            0x52534345u /* "ECSR" */
+#define ECS_VERSION          1u
+#define ECS_IMAGE_HEADER     256u        /* bytes before panel 0 */
+#define ECS_UNIT_COLS        64u         /* block columns per unit of a g >= 2 set */
+#define ECS_LANE_ELEMS       16u         /* residual elements per lane unit */
+#define ECS_CHUNK_LANES      64u         /* lane units per residual chunk */
+#define ECS_MAX_DELTA        255u        /* R_P - 1 for 8-bit deltas */
+#define ECS_NUM_BTYPES       4           /* t = 0..3  <->  g = 2, 4, 8, 16 */
+
+/* Words (uint32) of the panel header, which occupies the first ECS_PANEL_HEADER bytes of a panel. */
+#define ECS_PANEL_HEADER     128u
+enum {
+    PH_ROW0 = 0,        /* first output row of the panel */
+    PH_NROWS = 1,       /* rows owned */
+    PH_NSLOTS = 2,      /* FP32 partial-sum slots; a row's slots are consecutive */
+    PH_NRLANES = 3,     /* residual lane units */
+    PH_NRENTRIES = 4,   /* residual row segments (one per row and chunk it appears in) */
+    PH_ROWSLOT_OFF = 5, /* byte offset in panel: uint16 first slot of each row, nrows + 1 entries */
+    PH_RCHUNK_OFF = 6,  /* byte offset in panel: EcsRChunk per residual chunk */
+    PH_RENTRY_OFF = 7,  /* byte offset in panel: EcsREntry per residual row segment */
+    PH_RD_OFF = 8,      /* byte offset in panel: residual deltas, 16 B per lane unit */
+    PH_RV_OFF = 9,      /* byte offset in panel: residual values, 2 x 16 B per lane unit, chunk-wise [k][lane] */
+    PH_NUNITS = 10,     /* +t: units of granularity 2 << t */
+    PH_UTAB_OFF = 14,   /* +t: byte offset in panel: per unit (1 + g) uint16 = base column, g slots */
+    PH_BD_OFF = 18,     /* +t: byte offset in panel: 64 delta bytes per unit */
+    PH_BV_OFF = 22,     /* +t: byte offset in panel: 128 * g value bytes per unit */
+    PH_PANEL_BYTES = 26,
+    PH_META_BYTES = 27
+};
+
+typedef struct EcsRChunk {
+    uint64_t head_mask;  /* bit l set: lane unit l starts a row segment (bit 0 always set) */
+    uint32_t entry0;     /* index of the first EcsREntry of this chunk */
+    uint32_t nlanes;     /* lane units in this chunk (64 except the last) */
+} EcsRChunk;
+
+typedef struct EcsREntry {
+    int32_t  c;          /* column before the segment's first element minus the sum of the deltas of all
+                            earlier lanes of the chunk: col(l, k) = c + exclusive_scan(l) + local_prefix(k) */
+    uint16_t slot;       /* where the segment's partial sum goes */
+    uint16_t row_local;  /* row - PH_ROW0 (used by the host decoder only) */
+} EcsREntry;
+
+typedef struct EcsImageHeader {
+    uint32_t magic, version;
+    uint32_t m, n;
+    uint32_t num_panels, threads_per_wg;
+    uint32_t panel_stride, meta_stride;
+    uint32_t max_slots, lds_bytes;
+    uint64_t image_bytes, nnz;
+} EcsImageHeader;
+
+#endif

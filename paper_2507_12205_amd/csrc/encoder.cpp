@@ -1,0 +1,765 @@
+// Offline phase of EC-SpMV on the host: row panels, hierarchical block extraction (paper Section 4,
+// Algorithms 1 and 2), clipping into fixed-size units and ordering (Section 5), EC-CSR encoding with 8-bit
+// delta indices, padding and the load permutation (Section 6), plus the decoder used for round-trip checks.
+#include "encoder.h"
+
+#include <algorithm>
+#include <atomic>
+#include <chrono>
+#include <cstring>
+#include <thread>
+
+namespace ecs {
+
+// ------------------------------------------------------------------------------------------------------
+// small helpers
+// ------------------------------------------------------------------------------------------------------
+
+template <class F>
+static void parallel_for(int64_t count, int threads, F &&body)
+{
+    if (count <= 0) return;
+    threads = (int)std::max<int64_t>(1, std::min<int64_t>(threads, count));
+    if (threads == 1) {
+        for (int64_t i = 0; i < count; ++i) body(i);
+        return;
+    }
+    std::atomic<int64_t> next(0);
+    std::vector<std::thread> pool;
+    pool.reserve(threads);
+    for (int t = 0; t < threads; ++t)
+        pool.emplace_back([&]() {
+            for (;;) {
+                int64_t i = next.fetch_add(1);
+                if (i >= count) break;
+                body(i);
+            }
+        });
+    for (auto &th : pool) th.join();
+}
+
+static inline uint32_t align_up(uint32_t v, uint32_t a) { return (v + a - 1) / a * a; }
+
+static int resolve_threads(int req)
+{
+    if (req > 0) return std::min(req, 64);
+    unsigned hc = std::thread::hardware_concurrency();
+    if (hc == 0) hc = 1;
+    return (int)std::min<unsigned>(hc, 16);
+}
+
+// ------------------------------------------------------------------------------------------------------
+// CSR input
+// ------------------------------------------------------------------------------------------------------
+
+int csr_from_dense(const uint16_t *W, int64_t m, int64_t n, int64_t ld, int threads, Csr &out)
+{
+    out.m = m;
+    out.n = n;
+    out.rowptr.assign((size_t)m + 1, 0);
+    std::vector<int64_t> cnt((size_t)m, 0);
+    threads = resolve_threads(threads);
+    parallel_for(m, threads, [&](int64_t i) {
+        const uint16_t *row = W + i * ld;
+        int64_t c = 0;
+        for (int64_t j = 0; j < n; ++j) c += (row[j] & 0x7FFF) != 0;
+        cnt[(size_t)i] = c;
+    });
+    for (int64_t i = 0; i < m; ++i) out.rowptr[(size_t)i + 1] = out.rowptr[(size_t)i] + cnt[(size_t)i];
+    out.col.resize((size_t)out.rowptr[(size_t)m]);
+    out.val.resize((size_t)out.rowptr[(size_t)m]);
+    parallel_for(m, threads, [&](int64_t i) {
+        const uint16_t *row = W + i * ld;
+        int64_t p = out.rowptr[(size_t)i];
+        for (int64_t j = 0; j < n; ++j)
+            if ((row[j] & 0x7FFF) != 0) {
+                out.col[(size_t)p] = (int32_t)j;
+                out.val[(size_t)p] = row[j];
+                ++p;
+            }
+    });
+    return 0;
+}
+
+int csr_from_csr(const int64_t *rowptr, const int32_t *col, const uint16_t *val, int64_t m, int64_t n, Csr &out)
+{
+    if (rowptr[0] != 0) return -1;
+    out.m = m;
+    out.n = n;
+    out.rowptr.assign((size_t)m + 1, 0);
+    out.col.clear();
+    out.val.clear();
+    out.col.reserve((size_t)rowptr[m]);
+    out.val.reserve((size_t)rowptr[m]);
+    for (int64_t i = 0; i < m; ++i) {
+        if (rowptr[i + 1] < rowptr[i]) return -1;
+        int64_t prev = -1;
+        for (int64_t p = rowptr[i]; p < rowptr[i + 1]; ++p) {
+            int64_t c = col[p];
+            if (c < 0 || c >= n || c <= prev) return -1;
+            prev = c;
+            if ((val[p] & 0x7FFF) != 0) {
+                out.col.push_back((int32_t)c);
+                out.val.push_back(val[p]);
+            }
+        }
+        out.rowptr[(size_t)i + 1] = (int64_t)out.col.size();
+    }
+    return 0;
+}
+
+// ------------------------------------------------------------------------------------------------------
+// hierarchical block extraction inside one panel
+// ------------------------------------------------------------------------------------------------------
+
+namespace {
+
+// One row of a level matrix (Algorithm 1's A_E / A_R).  At level l a row stands for 2^l original rows
+// (`members`) and a set bit at column c means all of them hold a stored entry at c (Section 4.2).
+struct LRow {
+    std::vector<uint64_t> bits;
+    int cnt = 0;
+    int child_a = -1, child_b = -1;   // the two rows of the level below this block was extracted from
+    std::vector<int> members;         // panel-local original rows, size 2^level
+};
+
+struct PanelUnits {
+    // extracted units per block type t (g = 2 << t): member rows (panel-local) and 64 sorted columns
+    struct U {
+        std::vector<int> rows;
+        uint16_t cols[ECS_UNIT_COLS];
+        int block_id;
+        int block_len;
+    };
+    std::vector<U> units[ECS_NUM_BTYPES];
+    std::vector<std::vector<int32_t>> resid;  // per panel-local row: sorted residual columns
+};
+
+inline int popcount_and(const uint64_t *a, const uint64_t *b, int nw)
+{
+    int s = 0;
+    for (int w = 0; w < nw; ++w) s += __builtin_popcountll(a[w] & b[w]);
+    return s;
+}
+
+// Columns of `bits` in increasing order.
+inline void list_bits(const std::vector<uint64_t> &bits, std::vector<int32_t> &out)
+{
+    out.clear();
+    for (size_t w = 0; w < bits.size(); ++w) {
+        uint64_t v = bits[w];
+        while (v) {
+            int b = __builtin_ctzll(v);
+            out.push_back((int32_t)(w * 64 + b));
+            v &= v - 1;
+        }
+    }
+}
+
+// Cut a sorted column list into units of 64 columns whose successive gaps fit an 8-bit delta (the
+// "adjacent columns within the range R_P" rule of Section 6.2 and the "multiples of the load quantum" rule
+// of Section 6.3.1, with the quantum being one unit).  Columns that end up in no unit go to `rest`.
+void form_units(const std::vector<int32_t> &cols, std::vector<int32_t> &taken, std::vector<int32_t> &rest)
+{
+    taken.clear();
+    rest.clear();
+    size_t start = 0;                 // start of the current candidate run inside cols
+    for (size_t i = 0; i < cols.size(); ++i) {
+        if (i > start && cols[i] - cols[i - 1] > (int32_t)ECS_MAX_DELTA) {
+            for (size_t k = start; k < i; ++k) rest.push_back(cols[k]);
+            start = i;
+        }
+        if (i + 1 - start == ECS_UNIT_COLS) {
+            for (size_t k = start; k <= i; ++k) taken.push_back(cols[k]);
+            start = i + 1;
+        }
+    }
+    for (size_t k = start; k < cols.size(); ++k) rest.push_back(cols[k]);
+}
+
+// Greedy row matching (Algorithm 2).  Rows are popped in order of decreasing column count (ties: lower
+// index first); the popped row takes the still unselected row with which it shares the most columns
+// (ties: lower index).  A pair is kept only if the shared count reaches one unit, otherwise the popped
+// row stays single this round.
+void row_matching(const std::vector<LRow> &rows, int nw, std::vector<std::pair<int, int>> &pairs)
+{
+    pairs.clear();
+    const int R = (int)rows.size();
+    std::vector<int> order;
+    order.reserve(R);
+    for (int i = 0; i < R; ++i)
+        if (rows[i].cnt >= (int)ECS_UNIT_COLS) order.push_back(i);
+    std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return rows[a].cnt > rows[b].cnt; });
+    std::vector<char> unselected(R, 0);
+    for (int i : order) unselected[i] = 1;
+    for (int a : order) {
+        if (!unselected[a]) continue;
+        unselected[a] = 0;
+        int best = -1, best_sim = 0;
+        for (int b = 0; b < R; ++b) {
+            if (!unselected[b]) continue;
+            if (rows[b].cnt <= best_sim) continue;          // cannot beat the current best
+            int sim = popcount_and(rows[a].bits.data(), rows[b].bits.data(), nw);
+            if (sim > best_sim) {
+                best_sim = sim;
+                best = b;
+            }
+        }
+        if (best >= 0 && best_sim >= (int)ECS_UNIT_COLS) {
+            pairs.emplace_back(a, best);
+            unselected[best] = 0;
+        }
+    }
+}
+
+void extract_panel(const Csr &A, int64_t row0, int nrows, int max_g, int max_rounds, PanelUnits &out)
+{
+    const int n = (int)A.n;
+    const int nw = (n + 63) / 64;
+    std::vector<std::vector<LRow>> levels(1);
+    levels[0].resize(nrows);
+    for (int r = 0; r < nrows; ++r) {
+        LRow &L = levels[0][r];
+        L.bits.assign(nw, 0);
+        L.members.assign(1, r);
+        for (int64_t p = A.rowptr[row0 + r]; p < A.rowptr[row0 + r + 1]; ++p) {
+            int c = A.col[p];
+            L.bits[c >> 6] |= 1ull << (c & 63);
+        }
+        L.cnt = (int)(A.rowptr[row0 + r + 1] - A.rowptr[row0 + r]);
+    }
+
+    std::vector<std::pair<int, int>> pairs;
+    std::vector<uint64_t> common(nw);
+    std::vector<int32_t> cols, taken, rest;
+
+    // Algorithm 1: multi-level aggregation (outer), multi-round extraction (inner).
+    for (int level = 0; (2 << level) <= max_g; ++level) {
+        std::vector<LRow> next;                     // blocks extracted at this level = rows of the next A_E
+        for (int round = 0; round < max_rounds; ++round) {
+            std::vector<LRow> &AR = levels[level];
+            row_matching(AR, nw, pairs);
+            bool any = false;
+            for (auto &pr : pairs) {
+                LRow &a = AR[pr.first], &b = AR[pr.second];
+                for (int w = 0; w < nw; ++w) common[w] = a.bits[w] & b.bits[w];
+                list_bits(common, cols);
+                form_units(cols, taken, rest);
+                if (taken.empty()) continue;
+                any = true;
+                LRow blk;
+                blk.bits.assign(nw, 0);
+                for (int32_t c : taken) {
+                    uint64_t bit = 1ull << (c & 63);
+                    blk.bits[c >> 6] |= bit;
+                    a.bits[c >> 6] &= ~bit;         // extracted entries leave A_R
+                    b.bits[c >> 6] &= ~bit;
+                }
+                blk.cnt = (int)taken.size();
+                a.cnt -= blk.cnt;
+                b.cnt -= blk.cnt;
+                blk.child_a = pr.first;
+                blk.child_b = pr.second;
+                blk.members = a.members;
+                blk.members.insert(blk.members.end(), b.members.begin(), b.members.end());
+                next.push_back(std::move(blk));
+            }
+            if (!any) break;
+        }
+        if (next.empty()) break;
+        levels.push_back(std::move(next));
+    }
+
+    // Decode what is left at every level into blocks of that level's granularity, coarsest first.  Columns
+    // of a level >= 1 row that no longer form a valid unit (a neighbour was lifted to a coarser block and the
+    // gap now exceeds the delta range) fall back to the two rows of the level below.
+    out.resid.assign(nrows, {});
+    int block_id = 0;
+    for (int level = (int)levels.size() - 1; level >= 1; --level) {
+        std::vector<LRow> &rows = levels[level];
+        const int t = level - 1;
+        for (LRow &L : rows) {
+            list_bits(L.bits, cols);
+            form_units(cols, taken, rest);
+            for (int32_t c : rest) {
+                uint64_t bit = 1ull << (c & 63);
+                LRow &ca = levels[level - 1][L.child_a], &cb = levels[level - 1][L.child_b];
+                ca.bits[c >> 6] |= bit;
+                cb.bits[c >> 6] |= bit;
+                ++ca.cnt;
+                ++cb.cnt;
+            }
+            const int nu = (int)(taken.size() / ECS_UNIT_COLS);
+            for (int u = 0; u < nu; ++u) {
+                PanelUnits::U unit;
+                unit.rows = L.members;
+                for (unsigned k = 0; k < ECS_UNIT_COLS; ++k) unit.cols[k] = (uint16_t)taken[u * ECS_UNIT_COLS + k];
+                unit.block_id = block_id;
+                unit.block_len = nu;
+                out.units[t].push_back(std::move(unit));
+            }
+            if (nu) ++block_id;
+        }
+    }
+    for (int r = 0; r < nrows; ++r) list_bits(levels[0][r].bits, out.resid[r]);
+}
+
+// value of W[row, col] (must be a stored entry)
+inline uint16_t value_at(const Csr &A, int64_t row, int32_t col)
+{
+    const int32_t *b = A.col.data() + A.rowptr[row], *e = A.col.data() + A.rowptr[row + 1];
+    const int32_t *p = std::lower_bound(b, e, col);
+    return (p != e && *p == col) ? A.val[(size_t)(p - A.col.data())] : (uint16_t)0;
+}
+
+struct PanelImage {
+    std::vector<uint8_t> bytes;
+    uint32_t meta_bytes = 0, nslots = 0;
+    int64_t value_bytes = 0, delta_bytes = 0, pad_elements = 0, gap_pads = 0;
+    int64_t nnz_by_g[5] = {0, 0, 0, 0, 0};
+    int64_t units_by_g[5] = {0, 0, 0, 0, 0};
+    int64_t delta_hist[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
+    int err = 0;
+};
+
+inline int hist_bin(unsigned d)
+{
+    if (d == 0) return 0;
+    int b = 1;
+    while (d > 1 && b < 8) {
+        d >>= 1;
+        ++b;
+    }
+    return b;
+}
+
+void encode_panel(const Csr &A, int64_t row0, int nrows, PanelUnits &pu, bool reorder, PanelImage &img)
+{
+    // ---- ordering (Section 5): sets by decreasing granularity (fixed by the layout); inside a set the
+    // units of longer blocks first.
+    if (reorder)
+        for (int t = 0; t < ECS_NUM_BTYPES; ++t)
+            std::stable_sort(pu.units[t].begin(), pu.units[t].end(),
+                             [](const PanelUnits::U &a, const PanelUnits::U &b) { return a.block_len > b.block_len; });
+
+    // ---- residual rows -> elements (delta, value) with gap fillers and tail padding -> lane units
+    struct LaneUnit {
+        uint8_t d[ECS_LANE_ELEMS];
+        uint16_t v[ECS_LANE_ELEMS];
+        int row;          // panel-local
+        int32_t before;   // column "before" the first element: col0 for a row's first unit (its delta is 0)
+        uint32_t total;   // sum of the 16 deltas
+    };
+    std::vector<LaneUnit> lanes;
+    for (int r = 0; r < nrows; ++r) {
+        const std::vector<int32_t> &cols = pu.resid[r];
+        if (cols.empty()) continue;
+        std::vector<uint8_t> ds;
+        std::vector<uint16_t> vs;
+        int32_t cur = cols[0];
+        ds.push_back(0);
+        vs.push_back(value_at(A, row0 + r, cols[0]));
+        for (size_t k = 1; k < cols.size(); ++k) {
+            int32_t gap = cols[k] - cur;
+            while (gap > (int32_t)ECS_MAX_DELTA) {       // explicit zero every R_P - 1 columns (Section 6.2)
+                ds.push_back((uint8_t)ECS_MAX_DELTA);
+                vs.push_back(0);
+                gap -= ECS_MAX_DELTA;
+                ++img.gap_pads;
+                ++img.pad_elements;
+            }
+            ds.push_back((uint8_t)gap);
+            vs.push_back(value_at(A, row0 + r, cols[k]));
+            cur = cols[k];
+            ++img.delta_hist[hist_bin((unsigned)gap)];
+        }
+        img.nnz_by_g[0] += (int64_t)cols.size();
+        while (ds.size() % ECS_LANE_ELEMS) {             // tail alignment: zero-valued elements on the last column
+            ds.push_back(0);
+            vs.push_back(0);
+            ++img.pad_elements;
+        }
+        int32_t before = cols[0];
+        for (size_t e = 0; e < ds.size(); e += ECS_LANE_ELEMS) {
+            LaneUnit lu;
+            lu.row = r;
+            lu.before = before;
+            lu.total = 0;
+            for (unsigned k = 0; k < ECS_LANE_ELEMS; ++k) {
+                lu.d[k] = ds[e + k];
+                lu.v[k] = vs[e + k];
+                lu.total += ds[e + k];
+            }
+            before += (int32_t)lu.total;
+            lanes.push_back(lu);
+        }
+    }
+    const uint32_t nlanes = (uint32_t)lanes.size();
+    const uint32_t nchunks = (nlanes + ECS_CHUNK_LANES - 1) / ECS_CHUNK_LANES;
+    img.units_by_g[0] = nlanes;
+
+    // ---- residual chunk tables
+    std::vector<EcsRChunk> rchunks(nchunks);
+    std::vector<EcsREntry> rentries;
+    for (uint32_t c = 0; c < nchunks; ++c) {
+        EcsRChunk &ch = rchunks[c];
+        ch.head_mask = 0;
+        ch.entry0 = (uint32_t)rentries.size();
+        ch.nlanes = std::min<uint32_t>(ECS_CHUNK_LANES, nlanes - c * ECS_CHUNK_LANES);
+        int64_t scan = 0;                                   // sum of totals of earlier lanes in this chunk
+        for (uint32_t l = 0; l < ch.nlanes; ++l) {
+            const LaneUnit &lu = lanes[c * ECS_CHUNK_LANES + l];
+            bool head = (l == 0) || (lanes[c * ECS_CHUNK_LANES + l - 1].row != lu.row);
+            if (head) {
+                ch.head_mask |= 1ull << l;
+                EcsREntry e;
+                e.c = (int32_t)(lu.before - scan);
+                e.slot = 0;
+                e.row_local = (uint16_t)lu.row;
+                rentries.push_back(e);
+            }
+            scan += lu.total;
+        }
+    }
+
+    // ---- slots: one per (unit, member row) and one per residual row segment; a row's slots are consecutive
+    std::vector<uint32_t> per_row(nrows, 0);
+    for (int t = 0; t < ECS_NUM_BTYPES; ++t)
+        for (auto &u : pu.units[t])
+            for (int r : u.rows) ++per_row[r];
+    for (auto &e : rentries) ++per_row[e.row_local];
+    std::vector<uint32_t> rowslot(nrows + 1, 0);
+    for (int r = 0; r < nrows; ++r) rowslot[r + 1] = rowslot[r] + per_row[r];
+    img.nslots = rowslot[nrows];
+    if (img.nslots > 65535u || nrows > 65535) {
+        img.err = -2;
+        return;
+    }
+    std::vector<uint32_t> cursor(rowslot.begin(), rowslot.end() - 1);
+
+    // ---- layout
+    uint32_t off = ECS_PANEL_HEADER;
+    uint32_t hdr[ECS_PANEL_HEADER / 4];
+    std::memset(hdr, 0, sizeof(hdr));
+    hdr[PH_ROW0] = (uint32_t)row0;
+    hdr[PH_NROWS] = (uint32_t)nrows;
+    hdr[PH_NSLOTS] = img.nslots;
+    hdr[PH_NRLANES] = nlanes;
+    hdr[PH_NRENTRIES] = (uint32_t)rentries.size();
+    hdr[PH_ROWSLOT_OFF] = off;
+    off = align_up(off + 2u * (uint32_t)(nrows + 1), 16);
+    for (int t = ECS_NUM_BTYPES - 1; t >= 0; --t) {
+        const uint32_t g = 2u << t;
+        hdr[PH_NUNITS + t] = (uint32_t)pu.units[t].size();
+        hdr[PH_UTAB_OFF + t] = off;
+        off = align_up(off + 2u * (1 + g) * (uint32_t)pu.units[t].size(), 16);
+    }
+    hdr[PH_RCHUNK_OFF] = off;
+    off += (uint32_t)sizeof(EcsRChunk) * nchunks;
+    hdr[PH_RENTRY_OFF] = off;
+    off = align_up(off + (uint32_t)sizeof(EcsREntry) * (uint32_t)rentries.size(), 16);
+    img.meta_bytes = off;
+    hdr[PH_META_BYTES] = off;
+    for (int t = ECS_NUM_BTYPES - 1; t >= 0; --t) {
+        const uint32_t g = 2u << t;
+        const uint32_t nu = (uint32_t)pu.units[t].size();
+        hdr[PH_BD_OFF + t] = off;
+        off += 64u * nu;                  // multiple of 16
+        hdr[PH_BV_OFF + t] = off;
+        off += 128u * g * nu;
+        img.delta_bytes += 64ll * nu;
+        img.value_bytes += 128ll * g * nu;
+        img.units_by_g[t + 1] = nu;
+        img.nnz_by_g[t + 1] = (int64_t)nu * ECS_UNIT_COLS * g;
+    }
+    hdr[PH_RD_OFF] = off;
+    off += 16u * nlanes;
+    hdr[PH_RV_OFF] = off;
+    off += 32u * nlanes;
+    img.delta_bytes += 16ll * nlanes;
+    img.value_bytes += 32ll * nlanes;
+    off = align_up(off, 256);
+    hdr[PH_PANEL_BYTES] = off;
+    img.bytes.assign(off, 0);
+    uint8_t *P = img.bytes.data();
+
+    // ---- block sets
+    for (int t = ECS_NUM_BTYPES - 1; t >= 0; --t) {
+        const uint32_t g = 2u << t;
+        uint16_t *utab = (uint16_t *)(P + hdr[PH_UTAB_OFF + t]);
+        std::vector<uint16_t> flat(ECS_UNIT_COLS * g);
+        for (size_t u = 0; u < pu.units[t].size(); ++u) {
+            const PanelUnits::U &un = pu.units[t][u];
+            uint16_t *ue = utab + u * (1 + g);
+            ue[0] = un.cols[0];
+            for (uint32_t r = 0; r < g; ++r) ue[1 + r] = (uint16_t)cursor[un.rows[r]]++;
+            uint8_t *d = P + hdr[PH_BD_OFF + t] + 64u * u;
+            d[0] = 0;
+            for (unsigned k = 1; k < ECS_UNIT_COLS; ++k) d[k] = (uint8_t)(un.cols[k] - un.cols[k - 1]);
+            for (unsigned k = 0; k < ECS_UNIT_COLS; ++k)
+                for (uint32_t r = 0; r < g; ++r) flat[k * g + r] = value_at(A, row0 + un.rows[r], un.cols[k]);
+            // permutation: lane j owns flat[4*j*g, 4*(j+1)*g); its k-th group of 8 halfs goes to k*128 + 8*j
+            uint16_t *v = (uint16_t *)(P + hdr[PH_BV_OFF + t] + 128u * g * u);
+            for (uint32_t j = 0; j < 16; ++j)
+                for (uint32_t k = 0; k < g / 2; ++k)
+                    for (uint32_t i = 0; i < 8; ++i) v[k * 128 + 8 * j + i] = flat[4 * j * g + 8 * k + i];
+        }
+    }
+
+    // ---- residual set
+    for (uint32_t c = 0; c < nchunks; ++c) {
+        const uint32_t nl = rchunks[c].nlanes;
+        uint8_t *d = P + hdr[PH_RD_OFF] + 1024u * c;
+        uint16_t *v = (uint16_t *)(P + hdr[PH_RV_OFF] + 2048u * c);
+        for (uint32_t l = 0; l < nl; ++l) {
+            const LaneUnit &lu = lanes[c * ECS_CHUNK_LANES + l];
+            std::memcpy(d + 16u * l, lu.d, 16);
+            for (uint32_t i = 0; i < 8; ++i) {
+                v[8 * l + i] = lu.v[i];                 // first 128-bit load of lane l
+                v[8 * nl + 8 * l + i] = lu.v[8 + i];    // second
+            }
+        }
+    }
+    for (auto &e : rentries) e.slot = (uint16_t)cursor[e.row_local]++;
+    for (int r = 0; r < nrows; ++r)
+        if (cursor[r] != rowslot[r + 1]) img.err = -100;
+
+    std::memcpy(P, hdr, sizeof(hdr));
+    uint16_t *rs = (uint16_t *)(P + hdr[PH_ROWSLOT_OFF]);
+    for (int r = 0; r <= nrows; ++r) rs[r] = (uint16_t)rowslot[r];
+    if (nchunks) std::memcpy(P + hdr[PH_RCHUNK_OFF], rchunks.data(), sizeof(EcsRChunk) * nchunks);
+    if (!rentries.empty()) std::memcpy(P + hdr[PH_RENTRY_OFF], rentries.data(), sizeof(EcsREntry) * rentries.size());
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------------------------------------------
+// build
+// ------------------------------------------------------------------------------------------------------
+
+int build_image(const Csr &A, const BuildParams &bp, Image &out)
+{
+    auto t0 = std::chrono::steady_clock::now();
+    const int64_t m = A.m, n = A.n;
+    if (n > 65535 || m > 0x7fffffff) return -2;
+    const int64_t nnz = A.rowptr[(size_t)m];
+    int P = bp.num_panels;
+    if (P <= 0) P = (int)std::min<int64_t>(256, std::max<int64_t>(1, m / 16));
+    if (bp.global_matching) P = 1;
+    P = (int)std::min<int64_t>(P, m);
+
+    // nnz-balanced contiguous row panels (Section 5: even work per processing unit): panel p ends at the
+    // first row where the running nnz reaches (p + 1) / P of the total; ties in rows for empty matrices.
+    std::vector<int64_t> bound(P + 1, 0);
+    {
+        int64_t r = 0;
+        for (int p = 0; p < P; ++p) {
+            bound[p] = r;
+            const int64_t rows_left = m - r, panels_left = P - p;
+            int64_t take;
+            if (nnz == 0) {
+                take = (rows_left + panels_left - 1) / panels_left;
+            } else {
+                const double target = (double)nnz * (p + 1) / P;
+                int64_t e = r;
+                while (e < m && (double)A.rowptr[(size_t)e + 1] <= target) ++e;
+                // also take the row that crosses the target if that lands closer to it
+                if (e < m && (double)A.rowptr[(size_t)e + 1] - target < target - (double)A.rowptr[(size_t)e]) ++e;
+                take = e - r;
+            }
+            take = std::max<int64_t>(take, 1);                               // every panel owns at least one row
+            take = std::min<int64_t>(take, rows_left - (panels_left - 1));   // and leaves one for each later panel
+            r += take;
+        }
+        bound[P] = m;                                                        // the last panel ends at m
+    }
+    std::vector<PanelImage> imgs(P);
+    const int threads = resolve_threads(bp.num_threads);
+    parallel_for(P, threads, [&](int64_t p) {
+        const int64_t r0 = bound[p], r1 = (p + 1 == P) ? m : bound[p + 1];
+        PanelUnits pu;
+        extract_panel(A, r0, (int)(r1 - r0), bp.max_granularity, bp.max_rounds, pu);
+        encode_panel(A, r0, (int)(r1 - r0), pu, bp.reorder, imgs[p]);
+    });
+    uint32_t stride = 256, meta = 16, slots = 1;
+    for (auto &im : imgs) {
+        if (im.err) return im.err;
+        stride = std::max<uint32_t>(stride, (uint32_t)im.bytes.size());
+        meta = std::max(meta, im.meta_bytes);
+        slots = std::max(slots, im.nslots);
+    }
+    meta = align_up(meta, 16);
+    const uint64_t total = ECS_IMAGE_HEADER + (uint64_t)stride * (uint64_t)P;
+    if (total > 0xFFFFFFFF00ull) return -2;
+    out.bytes.assign((size_t)total, 0);
+    out.m = m;
+    out.n = n;
+    out.nnz = nnz;
+    out.num_panels = P;
+    out.threads_per_wg = bp.threads_per_wg;
+    out.panel_stride = stride;
+    out.meta_stride = meta;
+    out.max_slots = slots;
+    const uint32_t x_bytes = align_up((uint32_t)n * 2u, 16);
+    out.lds_bytes = x_bytes + meta + align_up(slots * 4u, 16);
+
+    ecspmv_stats_t &st = out.stats;
+    std::memset(&st, 0, sizeof(st));
+    st.struct_size = sizeof(st);
+    st.m = m;
+    st.n = n;
+    st.nnz = nnz;
+    st.image_bytes = (int64_t)total;
+    st.csr32_bytes = 6 * nnz + 4 * (m + 1);
+    st.csr16_bytes = 4 * nnz + 4 * (m + 1);
+    st.num_panels = P;
+    st.threads_per_wg = bp.threads_per_wg;
+    st.panel_stride = stride;
+    st.meta_stride = meta;
+    st.lds_bytes = out.lds_bytes;
+    st.min_panel_bytes = INT64_MAX;
+    for (int p = 0; p < P; ++p) {
+        PanelImage &im = imgs[p];
+        std::memcpy(out.bytes.data() + ECS_IMAGE_HEADER + (size_t)stride * p, im.bytes.data(), im.bytes.size());
+        st.value_bytes += im.value_bytes;
+        st.delta_bytes += im.delta_bytes;
+        st.meta_bytes += im.meta_bytes;
+        st.pad_elements += im.pad_elements;
+        st.gap_pad_elements += im.gap_pads;
+        st.max_panel_bytes = std::max<int64_t>(st.max_panel_bytes, (int64_t)im.bytes.size());
+        st.min_panel_bytes = std::min<int64_t>(st.min_panel_bytes, (int64_t)im.bytes.size());
+        for (int k = 0; k < 5; ++k) {
+            st.nnz_by_g[k] += im.nnz_by_g[k];
+            st.units_by_g[k] += im.units_by_g[k];
+        }
+        for (int k = 0; k < 9; ++k) st.delta_hist[k] += im.delta_hist[k];
+    }
+    st.meta_bytes += ECS_IMAGE_HEADER;
+    st.slack_bytes = st.image_bytes - st.value_bytes - st.delta_bytes - st.meta_bytes;
+    for (int k = 0; k < 5; ++k) st.x_access_cost += (double)st.nnz_by_g[k] / (double)(1 << k);
+
+    EcsImageHeader ih;
+    std::memset(&ih, 0, sizeof(ih));
+    ih.magic = ECS_MAGIC;
+    ih.version = ECS_VERSION;
+    ih.m = (uint32_t)m;
+    ih.n = (uint32_t)n;
+    ih.num_panels = (uint32_t)P;
+    ih.threads_per_wg = (uint32_t)bp.threads_per_wg;
+    ih.panel_stride = stride;
+    ih.meta_stride = meta;
+    ih.max_slots = slots;
+    ih.lds_bytes = out.lds_bytes;
+    ih.image_bytes = total;
+    ih.nnz = (uint64_t)nnz;
+    std::memcpy(out.bytes.data(), &ih, sizeof(ih));
+    st.build_seconds = std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count();
+    return 0;
+}
+
+// ------------------------------------------------------------------------------------------------------
+// decode: walk the image as the kernel does
+// ------------------------------------------------------------------------------------------------------
+
+namespace {
+
+struct PanelView {
+    const uint8_t *P;
+    const uint32_t *hdr;
+    const uint16_t *rowslot;
+    uint32_t nrows;
+    int row_of_slot(uint32_t s) const
+    {
+        // rowslot is non-decreasing; the owner of slot s is the last row whose first slot is <= s
+        const uint16_t *e = std::upper_bound(rowslot, rowslot + nrows + 1, (uint16_t)s);
+        return (int)(e - rowslot) - 1;
+    }
+};
+
+}  // namespace
+
+int walk_image(const Image &im, Triples *tri, BlockSets *bs)
+{
+    const uint8_t *base = im.bytes.data() + ECS_IMAGE_HEADER;
+    for (int p = 0; p < im.num_panels; ++p) {
+        PanelView pv;
+        pv.P = base + (size_t)im.panel_stride * p;
+        pv.hdr = (const uint32_t *)pv.P;
+        pv.nrows = pv.hdr[PH_NROWS];
+        pv.rowslot = (const uint16_t *)(pv.P + pv.hdr[PH_ROWSLOT_OFF]);
+        const uint32_t row0 = pv.hdr[PH_ROW0];
+        for (int t = ECS_NUM_BTYPES - 1; t >= 0; --t) {
+            const uint32_t g = 2u << t, nu = pv.hdr[PH_NUNITS + t];
+            const uint16_t *utab = (const uint16_t *)(pv.P + pv.hdr[PH_UTAB_OFF + t]);
+            for (uint32_t u = 0; u < nu; ++u) {
+                const uint16_t *ue = utab + u * (1 + g);
+                const uint8_t *d = pv.P + pv.hdr[PH_BD_OFF + t] + 64u * u;
+                const uint16_t *v = (const uint16_t *)(pv.P + pv.hdr[PH_BV_OFF + t] + 128u * g * u);
+                int32_t cols[ECS_UNIT_COLS];
+                // 16 lanes x 4 columns: local prefix inside a lane, exclusive scan over lanes, plus base
+                uint32_t lane_excl = 0;
+                for (uint32_t j = 0; j < 16; ++j) {
+                    uint32_t rel = 0;
+                    for (uint32_t c = 0; c < 4; ++c) {
+                        rel += d[4 * j + c];
+                        cols[4 * j + c] = (int32_t)(ue[0] + lane_excl + rel);
+                    }
+                    lane_excl += rel;
+                }
+                int rows[16];
+                for (uint32_t r = 0; r < g; ++r) {
+                    rows[r] = pv.row_of_slot(ue[1 + r]);
+                    if (rows[r] < 0 || rows[r] >= (int)pv.nrows) return -100;
+                }
+                if (bs) {
+                    bs->g.push_back((int32_t)g);
+                    for (uint32_t r = 0; r < g; ++r) bs->rows.push_back((int32_t)(row0 + rows[r]));
+                    for (uint32_t k = 0; k < ECS_UNIT_COLS; ++k) bs->cols.push_back(cols[k]);
+                }
+                if (tri)
+                    for (uint32_t j = 0; j < 16; ++j)
+                        for (uint32_t k = 0; k < g / 2; ++k)
+                            for (uint32_t i = 0; i < 8; ++i) {
+                                const uint32_t f = 8 * k + i;          // index in lane j's run
+                                const uint32_t c = f / g, r = f % g;
+                                const uint16_t val = v[k * 128 + 8 * j + i];
+                                if ((val & 0x7FFF) == 0) continue;
+                                tri->rows.push_back((int32_t)(row0 + rows[r]));
+                                tri->cols.push_back(cols[4 * j + c]);
+                                tri->vals.push_back(val);
+                            }
+            }
+        }
+        if (!tri) continue;
+        const uint32_t nlanes = pv.hdr[PH_NRLANES];
+        const uint32_t nchunks = (nlanes + ECS_CHUNK_LANES - 1) / ECS_CHUNK_LANES;
+        const EcsRChunk *rch = (const EcsRChunk *)(pv.P + pv.hdr[PH_RCHUNK_OFF]);
+        const EcsREntry *ren = (const EcsREntry *)(pv.P + pv.hdr[PH_RENTRY_OFF]);
+        for (uint32_t c = 0; c < nchunks; ++c) {
+            const uint32_t nl = std::min<uint32_t>(ECS_CHUNK_LANES, nlanes - c * ECS_CHUNK_LANES);
+            if (rch[c].nlanes != nl || !(rch[c].head_mask & 1)) return -101;
+            const uint8_t *d = pv.P + pv.hdr[PH_RD_OFF] + 1024u * c;
+            const uint16_t *v = (const uint16_t *)(pv.P + pv.hdr[PH_RV_OFF] + 2048u * c);
+            int64_t excl = 0;
+            for (uint32_t l = 0; l < nl; ++l) {
+                const uint64_t below = rch[c].head_mask & ((l == 63) ? ~0ull : ((2ull << l) - 1));
+                const EcsREntry &e = ren[rch[c].entry0 + (uint32_t)__builtin_popcountll(below) - 1];
+                const int row = pv.row_of_slot(e.slot);
+                if (row != (int)e.row_local) return -102;
+                int64_t rel = 0;
+                for (uint32_t k = 0; k < ECS_LANE_ELEMS; ++k) {
+                    rel += d[16 * l + k];
+                    const uint16_t val = (k < 8) ? v[8 * l + k] : v[8 * nl + 8 * l + (k - 8)];
+                    if ((val & 0x7FFF) == 0) continue;
+                    tri->rows.push_back((int32_t)(row0 + row));
+                    tri->cols.push_back((int32_t)(e.c + excl + rel));
+                    tri->vals.push_back(val);
+                }
+                excl += rel;
+            }
+        }
+    }
+    return 0;
+}
+
+}  // namespace ecs

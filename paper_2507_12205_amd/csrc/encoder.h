@@ -1,0 +1,53 @@
+// Host-side data structures of the offline phase (see encoder.cpp).
+#ifndef ECSPMV_ENCODER_H
+#define ECSPMV_ENCODER_H
+
+#include <cstdint>
+#include <vector>
+
+#include "../../include/ecspmv.h"
+#include "ecspmv_format.h"
+
+namespace ecs {
+
+struct Csr {
+    int64_t m = 0, n = 0;
+    std::vector<int64_t> rowptr;
+    std::vector<int32_t> col;
+    std::vector<uint16_t> val;
+};
+
+struct BuildParams {
+    int max_granularity = 8;
+    int max_rounds = 64;
+    int num_panels = 0;
+    int num_threads = 0;
+    int threads_per_wg = 1024;
+    bool global_matching = false;
+    bool reorder = true;
+};
+
+struct Image {
+    std::vector<uint8_t> bytes;
+    int64_t m = 0, n = 0, nnz = 0;
+    int num_panels = 0, threads_per_wg = 1024;
+    uint32_t panel_stride = 0, meta_stride = 0, max_slots = 0, lds_bytes = 0;
+    ecspmv_stats_t stats;
+};
+
+struct Triples {
+    std::vector<int32_t> rows, cols;
+    std::vector<uint16_t> vals;
+};
+
+struct BlockSets {
+    std::vector<int32_t> g, rows, cols;
+};
+
+int csr_from_dense(const uint16_t *W, int64_t m, int64_t n, int64_t ld, int threads, Csr &out);
+int csr_from_csr(const int64_t *rowptr, const int32_t *col, const uint16_t *val, int64_t m, int64_t n, Csr &out);
+int build_image(const Csr &A, const BuildParams &bp, Image &out);
+int walk_image(const Image &im, Triples *tri, BlockSets *bs);
+
+}  // namespace ecs
+#endif

@@ -1,0 +1,420 @@
+// Online phase of EC-SpMV for CDNA4 (gfx950): y = W x over the EC-CSR image (paper Section 7), plus the
+// plain CSR comparison kernel and a streaming-read kernel that measures the achievable HBM read rate.
+//
+// One workgroup per row panel.  The workgroup stages x and the panel's tables in LDS once, then its
+// wavefronts stream the panel's delta and value arrays with 128-bit loads, rebuild absolute columns with
+// cross-lane prefix scans (DPP), gather x from LDS, accumulate in FP32, reduce across lanes, and leave one
+// FP32 partial per (unit, row) in an LDS slot.  After a barrier the slots of each row are added in a fixed
+// order and the row is stored as FP16.  No atomics, no pre-zeroed y, bit-reproducible results.
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+#include <stdint.h>
+
+#include "ecspmv_format.h"
+#include "launch.h"
+
+namespace {
+
+// ---- cross-lane helpers (DPP).  With bound_ctrl = 0 a lane whose source lane does not exist keeps `old`.
+template <int CTRL, int ROW_MASK = 0xF>
+__device__ __forceinline__ int dpp_i(int old, int src)
+{
+    return __builtin_amdgcn_update_dpp(old, src, CTRL, ROW_MASK, 0xF, false);
+}
+template <int CTRL, int ROW_MASK = 0xF>
+__device__ __forceinline__ float dpp_f(float old, float src)
+{
+    return __int_as_float(
+        __builtin_amdgcn_update_dpp(__float_as_int(old), __float_as_int(src), CTRL, ROW_MASK, 0xF, false));
+}
+
+constexpr int DPP_ROW_SHR1 = 0x111, DPP_ROW_SHR2 = 0x112, DPP_ROW_SHR4 = 0x114, DPP_ROW_SHR8 = 0x118;
+constexpr int DPP_ROW_BCAST15 = 0x142, DPP_ROW_BCAST31 = 0x143;
+constexpr int DPP_QUAD_1032 = 0xB1, DPP_QUAD_2301 = 0x4E, DPP_ROW_HALF_MIRROR = 0x141, DPP_ROW_MIRROR = 0x140;
+
+// inclusive prefix sum over the 16 lanes of a DPP row
+__device__ __forceinline__ int row16_incl_scan(int v)
+{
+    v += dpp_i<DPP_ROW_SHR1>(0, v);
+    v += dpp_i<DPP_ROW_SHR2>(0, v);
+    v += dpp_i<DPP_ROW_SHR4>(0, v);
+    v += dpp_i<DPP_ROW_SHR8>(0, v);
+    return v;
+}
+
+// inclusive prefix sum over the 64 lanes of the wavefront
+__device__ __forceinline__ int wave64_incl_scan(int v)
+{
+    v = row16_incl_scan(v);
+    v += dpp_i<DPP_ROW_BCAST15, 0xA>(0, v);   // rows 1 and 3 take the total of rows 0 and 2
+    v += dpp_i<DPP_ROW_BCAST31, 0xC>(0, v);   // rows 2 and 3 take the total of rows 0..1
+    return v;
+}
+
+// inclusive segmented sum over the wavefront: `head` is 1 on the first lane of a segment
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ void seg_step(float &v, int &head)
+{
+    const float tv = dpp_f<CTRL, ROW_MASK>(0.0f, v);
+    const int th = dpp_i<CTRL, ROW_MASK>(0, head);
+    v = head ? v : v + tv;
+    head |= th;
+}
+__device__ __forceinline__ float wave64_seg_incl_scan(float v, int head)
+{
+    seg_step<DPP_ROW_SHR1, 0xF>(v, head);
+    seg_step<DPP_ROW_SHR2, 0xF>(v, head);
+    seg_step<DPP_ROW_SHR4, 0xF>(v, head);
+    seg_step<DPP_ROW_SHR8, 0xF>(v, head);
+    seg_step<DPP_ROW_BCAST15, 0xA>(v, head);
+    seg_step<DPP_ROW_BCAST31, 0xC>(v, head);
+    return v;
+}
+
+// sum over the 16 lanes of a DPP row, result in every lane
+__device__ __forceinline__ float row16_allreduce(float a)
+{
+    a += dpp_f<DPP_QUAD_1032>(0.0f, a);
+    a += dpp_f<DPP_QUAD_2301>(0.0f, a);
+    a += dpp_f<DPP_ROW_HALF_MIRROR>(0.0f, a);
+    a += dpp_f<DPP_ROW_MIRROR>(0.0f, a);
+    return a;
+}
+
+__device__ __forceinline__ float half_bits_to_float(uint32_t h)
+{
+    return __half2float(__ushort_as_half((unsigned short)h));
+}
+
+// acc += w * x with FP16 inputs taken exactly and FP32 accumulation
+__device__ __forceinline__ float fma_h(uint32_t w_bits, float xf, float acc)
+{
+    return fmaf(half_bits_to_float(w_bits), xf, acc);
+}
+
+__device__ __forceinline__ uint4 load16(const uint8_t *p) { return *reinterpret_cast<const uint4 *>(p); }
+
+struct Ctx {
+    const uint8_t *panel;      // global
+    const uint16_t *xs;        // LDS: x as FP16 bits
+    const uint8_t *meta;       // LDS copy of the panel's meta region
+    float *slots;              // LDS partial sums
+    int wave, lane, nwaves;
+};
+
+// ---- g >= 2 block sets: a DPP row of 16 lanes takes one unit (64 columns), 4 columns per lane.
+template <int G>
+struct UnitRegs {
+    uint32_t d;            // 4 delta bytes
+    uint4 v[G / 2];        // 4 * G FP16 values of this lane
+};
+
+template <int G>
+__device__ __forceinline__ void load_unit(const Ctx &c, const uint8_t *bd, const uint8_t *bv, uint32_t u, uint32_t nu,
+                                          UnitRegs<G> &r)
+{
+    const int j = c.lane & 15;
+    if (u < nu) {
+        r.d = *reinterpret_cast<const uint32_t *>(bd + 64u * u + 4u * j);
+#pragma unroll
+        for (int k = 0; k < G / 2; ++k) r.v[k] = load16(bv + (size_t)(128u * G) * u + 256u * k + 16u * j);
+    } else {
+        r.d = 0;
+#pragma unroll
+        for (int k = 0; k < G / 2; ++k) r.v[k] = make_uint4(0, 0, 0, 0);
+    }
+}
+
+template <int G>
+__device__ __forceinline__ void compute_unit(const Ctx &c, const uint16_t *utab, uint32_t u, uint32_t nu,
+                                             const UnitRegs<G> &r)
+{
+    const int j = c.lane & 15;
+    // delta decode: local prefix over the lane's 4 columns, exclusive scan over the 16 lanes, unit base
+    uint32_t rel[4];
+    rel[0] = r.d & 0xFF;
+    rel[1] = rel[0] + ((r.d >> 8) & 0xFF);
+    rel[2] = rel[1] + ((r.d >> 16) & 0xFF);
+    rel[3] = rel[2] + (r.d >> 24);
+    const int incl = row16_incl_scan((int)rel[3]);
+    const bool active = u < nu;
+    const uint16_t *ue = utab + (active ? u : 0) * (1 + G);
+    const uint32_t start = (active ? (uint32_t)ue[0] : 0u) + (uint32_t)incl - rel[3];
+    float xv[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) xv[k] = active ? half_bits_to_float(c.xs[start + rel[k]]) : 0.0f;
+    float acc[G];
+#pragma unroll
+    for (int q = 0; q < G; ++q) acc[q] = 0.0f;
+    const uint32_t *w = reinterpret_cast<const uint32_t *>(r.v);   // 2 * G dwords, 2 halfs each
+#pragma unroll
+    for (int f = 0; f < 4 * G; ++f) {                              // f = column * G + row
+        const uint32_t word = w[f >> 1];
+        const uint32_t hb = (f & 1) ? (word >> 16) : (word & 0xFFFF);
+        acc[f % G] = fma_h(hb, xv[f / G], acc[f % G]);
+    }
+#pragma unroll
+    for (int q = 0; q < G; ++q) acc[q] = row16_allreduce(acc[q]);
+    float out = acc[0];
+#pragma unroll
+    for (int q = 1; q < G; ++q) out = (j == q) ? acc[q] : out;
+    if (active && j < G) c.slots[ue[1 + j]] = out;
+}
+
+template <int G>
+__device__ __forceinline__ void run_block_set(const Ctx &c, const uint32_t *hdr, int t)
+{
+    const uint32_t nu = hdr[PH_NUNITS + t];
+    if (nu == 0) return;
+    const uint8_t *bd = c.panel + hdr[PH_BD_OFF + t];
+    const uint8_t *bv = c.panel + hdr[PH_BV_OFF + t];
+    const uint16_t *utab = reinterpret_cast<const uint16_t *>(c.meta + hdr[PH_UTAB_OFF + t]);
+    const uint32_t step = 4u * c.nwaves;
+    uint32_t u0 = 4u * c.wave;                      // wave-uniform
+    if (u0 >= nu) return;
+    UnitRegs<G> cur, nxt;
+    load_unit<G>(c, bd, bv, u0 + (c.lane >> 4), nu, cur);
+    while (true) {
+        const uint32_t n0 = u0 + step;
+        const bool more = n0 < nu;
+        if (more) load_unit<G>(c, bd, bv, n0 + (c.lane >> 4), nu, nxt);   // prefetch while computing
+        compute_unit<G>(c, utab, u0 + (c.lane >> 4), nu, cur);
+        if (!more) break;
+        cur = nxt;
+        u0 = n0;
+    }
+}
+
+// ---- residual (1-grained) set: a wavefront takes a chunk of 64 lane units, 16 elements per lane.
+struct ChunkRegs {
+    uint4 d;      // 16 delta bytes
+    uint4 v0, v1; // 16 FP16 values
+};
+
+__device__ __forceinline__ void load_chunk(const Ctx &c, const uint8_t *rd, const uint8_t *rv, uint32_t ch, uint32_t nlanes,
+                                           ChunkRegs &r)
+{
+    const uint32_t nl = min(64u, nlanes - 64u * ch);
+    if ((uint32_t)c.lane < nl) {
+        r.d = load16(rd + 1024u * ch + 16u * c.lane);
+        r.v0 = load16(rv + 2048u * ch + 16u * c.lane);
+        r.v1 = load16(rv + 2048u * ch + 16u * nl + 16u * c.lane);
+    } else {
+        r.d = make_uint4(0, 0, 0, 0);
+        r.v0 = make_uint4(0, 0, 0, 0);
+        r.v1 = make_uint4(0, 0, 0, 0);
+    }
+}
+
+__device__ __forceinline__ void compute_chunk(const Ctx &c, const EcsRChunk *rch, const EcsREntry *ren, uint32_t ch,
+                                              uint32_t nlanes, const ChunkRegs &r)
+{
+    const uint32_t nl = min(64u, nlanes - 64u * ch);
+    const bool active = (uint32_t)c.lane < nl;
+    // lane-local inclusive prefix of the 16 deltas
+    uint32_t rel[16];
+    const uint32_t dw[4] = {r.d.x, r.d.y, r.d.z, r.d.w};
+    uint32_t run = 0;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        run += (dw[i >> 2] >> (8 * (i & 3))) & 0xFF;
+        rel[i] = run;
+    }
+    // wave64 prefix scan of the lane totals; the segment's entry folds base column and earlier lanes
+    const int incl = wave64_incl_scan((int)run);
+    const uint64_t mask = rch[ch].head_mask;
+    const uint64_t le = (c.lane == 63) ? ~0ull : ((2ull << c.lane) - 1ull);
+    const int seg = __popcll(mask & le) - 1;
+    const EcsREntry e = ren[rch[ch].entry0 + seg];
+    const int start = e.c + incl - (int)run;
+    float acc = 0.0f;
+    if (active) {
+        const uint32_t vw[8] = {r.v0.x, r.v0.y, r.v0.z, r.v0.w, r.v1.x, r.v1.y, r.v1.z, r.v1.w};
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const uint32_t word = vw[i >> 1];
+            const uint32_t hb = (i & 1) ? (word >> 16) : (word & 0xFFFF);
+            acc = fma_h(hb, half_bits_to_float(c.xs[start + (int)rel[i]]), acc);
+        }
+    }
+    // segmented wavefront reduction: the last lane of every row segment holds its sum
+    const int head = (int)((mask >> c.lane) & 1ull);
+    const float seg_sum = wave64_seg_incl_scan(acc, head);
+    const bool is_end = active && ((uint32_t)c.lane + 1 == nl || ((mask >> (c.lane + 1)) & 1ull));
+    if (is_end) c.slots[e.slot] = seg_sum;
+}
+
+__device__ __forceinline__ void run_residual(const Ctx &c, const uint32_t *hdr)
+{
+    const uint32_t nlanes = hdr[PH_NRLANES];
+    const uint32_t nch = (nlanes + 63u) >> 6;
+    uint32_t ch = c.wave;
+    if (ch >= nch) return;
+    const uint8_t *rd = c.panel + hdr[PH_RD_OFF];
+    const uint8_t *rv = c.panel + hdr[PH_RV_OFF];
+    const EcsRChunk *rch = reinterpret_cast<const EcsRChunk *>(c.meta + hdr[PH_RCHUNK_OFF]);
+    const EcsREntry *ren = reinterpret_cast<const EcsREntry *>(c.meta + hdr[PH_RENTRY_OFF]);
+    ChunkRegs cur, nxt;
+    load_chunk(c, rd, rv, ch, nlanes, cur);
+    while (true) {
+        const uint32_t nc = ch + c.nwaves;
+        const bool more = nc < nch;
+        if (more) load_chunk(c, rd, rv, nc, nlanes, nxt);
+        compute_chunk(c, rch, ren, ch, nlanes, cur);
+        if (!more) break;
+        cur = nxt;
+        ch = nc;
+    }
+}
+
+__global__ __launch_bounds__(1024) void ecspmv_kernel(const uint8_t *__restrict__ image, const uint16_t *__restrict__ x,
+                                                      uint16_t *__restrict__ y, uint32_t n, uint32_t panel_stride,
+                                                      uint32_t meta_stride, uint32_t x_bytes)
+{
+    extern __shared__ uint4 lds4[];
+    uint8_t *lds = reinterpret_cast<uint8_t *>(lds4);
+    uint16_t *xs = reinterpret_cast<uint16_t *>(lds);
+    uint8_t *meta = lds + x_bytes;
+    float *slots = reinterpret_cast<float *>(lds + x_bytes + meta_stride);
+
+    const uint32_t tid = threadIdx.x, nt = blockDim.x;
+    const uint8_t *panel = image + ECS_IMAGE_HEADER + (size_t)panel_stride * blockIdx.x;
+
+    // stage the panel's tables and the whole of x in LDS (x is read from HBM once per XCD, then from L2)
+    for (uint32_t i = tid; i < meta_stride / 16; i += nt)
+        reinterpret_cast<uint4 *>(meta)[i] = reinterpret_cast<const uint4 *>(panel)[i];
+    if ((reinterpret_cast<uintptr_t>(x) & 15) == 0) {
+        const uint32_t nvec = n / 8;
+        for (uint32_t i = tid; i < nvec; i += nt) lds4[i] = reinterpret_cast<const uint4 *>(x)[i];
+        for (uint32_t i = nvec * 8 + tid; i < n; i += nt) xs[i] = x[i];
+    } else {
+        for (uint32_t i = tid; i < n; i += nt) xs[i] = x[i];
+    }
+    __syncthreads();
+
+    const uint32_t *hdr = reinterpret_cast<const uint32_t *>(meta);
+    Ctx c;
+    c.panel = panel;
+    c.xs = xs;
+    c.meta = meta;
+    c.slots = slots;
+    c.wave = tid >> 6;
+    c.lane = tid & 63;
+    c.nwaves = nt >> 6;
+
+    run_block_set<16>(c, hdr, 3);
+    run_block_set<8>(c, hdr, 2);
+    run_block_set<4>(c, hdr, 1);
+    run_block_set<2>(c, hdr, 0);
+    run_residual(c, hdr);
+    __syncthreads();
+
+    // every row: add its slots in a fixed order (16 lanes stride over them, then a fixed tree), store FP16
+    const uint32_t nrows = hdr[PH_NROWS], row0 = hdr[PH_ROW0];
+    const uint16_t *rowslot = reinterpret_cast<const uint16_t *>(meta + hdr[PH_ROWSLOT_OFF]);
+    const uint32_t j = tid & 15;
+    for (uint32_t r = tid >> 4; r < nrows; r += nt >> 4) {
+        const uint32_t s0 = rowslot[r], s1 = rowslot[r + 1];
+        float sum = 0.0f;
+        for (uint32_t s = s0 + j; s < s1; s += 16) sum += slots[s];
+        sum = row16_allreduce(sum);
+        if (j == 0) y[row0 + r] = __half_as_ushort(__float2half_rn(sum));
+    }
+}
+
+// ---- plain CSR, one wavefront per row (comparison only)
+__global__ __launch_bounds__(256) void csr_kernel(const int32_t *__restrict__ rowptr, const int32_t *__restrict__ col,
+                                                  const uint16_t *__restrict__ val, const uint16_t *__restrict__ x,
+                                                  uint16_t *__restrict__ y, uint32_t m)
+{
+    const uint32_t row = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    const uint32_t lane = threadIdx.x & 63;
+    if (row >= m) return;
+    const int32_t b = rowptr[row], e = rowptr[row + 1];
+    float acc = 0.0f;
+    for (int32_t p = b + (int32_t)lane; p < e; p += 64) acc = fma_h(val[p], half_bits_to_float(x[col[p]]), acc);
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) acc += __shfl_down(acc, off, 64);
+    if (lane == 0) y[row] = __half_as_ushort(__float2half_rn(acc));
+}
+
+// ---- streaming read: every byte once, 128-bit loads, grid-stride, four loads in flight per lane
+__global__ __launch_bounds__(1024) void stream_read_kernel(const uint4 *__restrict__ buf, uint64_t nvec, uint32_t *__restrict__ out)
+{
+    const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+    uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    uint32_t acc = 0;
+    for (; i + 3 * stride < nvec; i += 4 * stride) {
+        const uint4 a = buf[i], b = buf[i + stride], c = buf[i + 2 * stride], d = buf[i + 3 * stride];
+        acc ^= a.x ^ a.y ^ a.z ^ a.w ^ b.x ^ b.y ^ b.z ^ b.w ^ c.x ^ c.y ^ c.z ^ c.w ^ d.x ^ d.y ^ d.z ^ d.w;
+    }
+    for (; i < nvec; i += stride) {
+        const uint4 a = buf[i];
+        acc ^= a.x ^ a.y ^ a.z ^ a.w;
+    }
+    __shared__ uint32_t red[16];
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) acc ^= __shfl_down(acc, off, 64);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t r = 0;
+        for (uint32_t w = 0; w < (blockDim.x >> 6); ++w) r ^= red[w];
+        out[blockIdx.x] = r;
+    }
+}
+
+}  // namespace
+
+namespace ecs {
+
+int launch_ecspmv(const void *d_image, const void *d_x, void *d_y, uint32_t n, uint32_t num_panels, uint32_t threads,
+                  uint32_t panel_stride, uint32_t meta_stride, uint32_t lds_bytes, void *stream)
+{
+    static thread_local uint32_t attr_set_for = 0;
+    if (lds_bytes > 65536 && lds_bytes > attr_set_for) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(ecspmv_kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+        if (e != hipSuccess) return (int)e;
+        attr_set_for = lds_bytes;
+    }
+    const uint32_t x_bytes = (n * 2u + 15u) / 16u * 16u;
+    hipLaunchKernelGGL(ecspmv_kernel, dim3(num_panels), dim3(threads), lds_bytes, (hipStream_t)stream,
+                       (const uint8_t *)d_image, (const uint16_t *)d_x, (uint16_t *)d_y, n, panel_stride, meta_stride,
+                       x_bytes);
+    return (int)hipGetLastError();
+}
+
+int launch_csr(const void *d_rowptr, const void *d_col, const void *d_val, const void *d_x, void *d_y, uint32_t m,
+               void *stream)
+{
+    const uint32_t rows_per_wg = 4;
+    hipLaunchKernelGGL(csr_kernel, dim3((m + rows_per_wg - 1) / rows_per_wg), dim3(64 * rows_per_wg), 0,
+                       (hipStream_t)stream, (const int32_t *)d_rowptr, (const int32_t *)d_col, (const uint16_t *)d_val,
+                       (const uint16_t *)d_x, (uint16_t *)d_y, m);
+    return (int)hipGetLastError();
+}
+
+int launch_stream_read(const void *d_buf, uint64_t bytes, void *d_out, uint32_t num_wg, void *stream)
+{
+    hipLaunchKernelGGL(stream_read_kernel, dim3(num_wg), dim3(1024), 0, (hipStream_t)stream, (const uint4 *)d_buf,
+                       bytes / 16, (uint32_t *)d_out);
+    return (int)hipGetLastError();
+}
+
+int copy_to_device(void *d_dst, const void *h_src, uint64_t bytes, void *stream)
+{
+    hipError_t e = hipMemcpyAsync(d_dst, h_src, bytes, hipMemcpyHostToDevice, (hipStream_t)stream);
+    if (e != hipSuccess) return (int)e;
+    return (int)hipStreamSynchronize((hipStream_t)stream);
+}
+
+int device_lds_limit(int *bytes)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return (int)e;
+    return (int)hipDeviceGetAttribute(bytes, hipDeviceAttributeMaxSharedMemoryPerBlock, dev);
+}
+
+}  // namespace ecs
