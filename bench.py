@@ -1,0 +1,286 @@
+#!/usr/bin/env python3
+"""Bench of the EC-SpMV hot path on one MI355X.
+
+Workload (default): the LLaMA-13B-shaped decoder layer at 70 % sparsity -- seven back-to-back SpMVs
+(q/k/v/o 5120x5120, gate/up 13824x5120, down 5120x13824) on one stream.  A "step" is one such layer.  The steps
+rotate through several independently seeded layers whose EC-CSR images total more than 1 GB, so that no matrix is
+served from the 256 MB Infinity Cache (cold-cache timing).  Inputs are synthetic (workloads/generators.py) and are
+resident in HBM before the timed region starts.
+
+Prints ONE JSON line: whole-job effective HBM GB/s (bytes that must be read or written per SpMV: EC-CSR values,
+deltas and tables + x + y, divided by time), microseconds per SpMV, the roofline of the SpMV kernel and the CPU
+oracle's rate on the host cores as a baseline.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+from concurrent.futures import ThreadPoolExecutor
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", type=int, default=3, help="workload config id (workloads/generators.py)")
+    ap.add_argument("--copies", type=int, default=0, help="seeded copies in the rotation set (0 = enough for the config's cold-cache size)")
+    ap.add_argument("--max-granularity", type=int, default=0)
+    ap.add_argument("--panels", type=int, default=0)
+    ap.add_argument("--threads-per-wg", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true", help="skip hot-cache, CSR and streaming-read legs")
+    ap.add_argument("--detail", type=str, default="", help="write per-shape details to this JSON file")
+    return ap.parse_args()
+
+
+def algorithmic_bytes(st) -> int:
+    """Bytes one SpMV must move: EC-CSR values + deltas + tables, x once, y once."""
+    return int(st.value_bytes + st.delta_bytes + st.meta_bytes + 2 * st.n + 2 * st.m)
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print(f"bench.py: this build runs on one GPU; --gpus {args.gpus} is not supported "
+              "(the path shards by row panels, see DESIGN.md), exiting", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    import paper_2507_12205_amd as E
+    from paper_2507_12205_amd import device as D
+    from workloads import generators as gen
+    E.binding.lib()
+
+    cfg = gen.config(args.config)
+    nshapes = len(cfg.shapes)
+    opts = E.make_opts(max_granularity=args.max_granularity, num_panels=args.panels,
+                       threads_per_wg=args.threads_per_wg)
+    torch.cuda.set_device(0)
+    stream = torch.cuda.current_stream()
+    sh = int(stream.cuda_stream)
+
+    # ---- build the rotation set -------------------------------------------------------------------------
+    t_prep = time.time()
+    est_layer_bytes = sum(2.9 * cfg.density * m * n for _, m, n in cfg.shapes)
+    copies = args.copies or max(2, int(np.ceil(max(cfg.rotation_bytes, 1) * 1.05 / est_layer_bytes)))
+    mats = []      # [copy][shape] -> dict
+
+    def make(job):
+        copy, sid = job
+        W = gen.make_matrix(cfg, sid, seed=0, copy=copy)
+        A = E.ecspmv_build_dense(W, opts)
+        return copy, sid, W, A
+
+    jobs = [(c, s) for c in range(copies) for s in range(nshapes)]
+    keep_dense = {}
+    with ThreadPoolExecutor(max_workers=4) as ex:
+        results = list(ex.map(make, jobs))
+    build_seconds = 0.0
+    for copy, sid, W, A in results:
+        while len(mats) <= copy:
+            mats.append([None] * nshapes)
+        st = A.ecspmv_stats()
+        build_seconds += st.build_seconds
+        D.upload(A, stream=stream)
+        m, n = W.shape
+        x = gen.make_vector(n, seed=0, cid=cfg.cid, shape_id=sid, copy=copy)
+        mats[copy][sid] = dict(A=A, st=st, x=torch.from_numpy(x.view(np.int16)).cuda().view(torch.float16),
+                               y=torch.empty(m, dtype=torch.float16, device="cuda"), bytes=algorithmic_bytes(st),
+                               name=cfg.shapes[sid][0], m=m, n=n)
+        if copy == 0:
+            keep_dense[sid] = (W, x)
+    del results
+    torch.cuda.synchronize()
+    t_prep = time.time() - t_prep
+    image_total = sum(e["st"].image_bytes for layer in mats for e in layer)
+    layer_bytes = [sum(e["bytes"] for e in layer) for layer in mats]
+
+    def run_layer(layer):
+        for e in layer:
+            e["A"].ecspmv_run(e["x"].data_ptr(), e["y"].data_ptr(), sh)
+
+    # ---- timed region: K steps, cold cache (rotation) ---------------------------------------------------
+    for w in range(args.warmup):
+        run_layer(mats[w % copies])
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record(stream)
+    for s in range(args.steps):
+        run_layer(mats[(args.warmup + s) % copies])
+    ev1.record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    gpu_ms = ev0.elapsed_time(ev1)
+    total_ms = max(gpu_ms, 0.0) if gpu_ms > 0 else wall * 1e3
+    nlaunch = args.steps * nshapes
+    moved = sum(layer_bytes[(args.warmup + s) % copies] for s in range(args.steps))
+    value = moved / (total_ms * 1e-3) / 1e9
+    us_per_spmv = total_ms * 1e3 / nlaunch
+
+    # ---- per-shape cold timings: one event-bracketed region per shape class, rotating over every matrix of that
+    # shape in the set (only classes whose images together exceed the 256 MB Infinity Cache count as cold)
+    classes = {}
+    for layer in mats:
+        for e in layer:
+            classes.setdefault((e["m"], e["n"]), []).append(e)
+    per_shape = {}
+    for (m, n), lst in classes.items():
+        tot_img = sum(int(e["st"].image_bytes) for e in lst)
+        reps = max(2, (args.steps * nshapes) // (4 * len(lst)))
+        for e in lst:
+            e["A"].ecspmv_run(e["x"].data_ptr(), e["y"].data_ptr(), sh)
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record(stream)
+        for _ in range(reps):
+            for e in lst:
+                e["A"].ecspmv_run(e["x"].data_ptr(), e["y"].data_ptr(), sh)
+        b.record(stream)
+        torch.cuda.synchronize()
+        us = a.elapsed_time(b) * 1e3 / (reps * len(lst))
+        byt = sum(e["bytes"] for e in lst) / len(lst)
+        per_shape[f"{m}x{n}"] = dict(us=round(us, 3), gbps=round(byt / us / 1e3, 1), bytes=int(byt),
+                                     cold=bool(tot_img > (300 << 20)), matrices=len(lst))
+    avg_launch_us = us_per_spmv
+    achieved = value
+    byte_sum, n_ev = moved, nlaunch
+
+    out = {
+        "metric": "effective HBM GB/s of cold-cache EC-CSR SpMV (EC-CSR bytes + x + y per SpMV / time)",
+        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(total_ms / args.steps, 6), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f16 values, f32 accumulate", "data": "synthetic",
+        "config": {"workload": f"config {cfg.cid} ({cfg.name}): {nshapes} SpMVs per step, "
+                               + ", ".join(f"{nm} {m}x{n}" for nm, m, n in cfg.shapes)
+                               + f"; density {cfg.density}; rotation of {copies} seeded copies, "
+                               f"{image_total / 2**20:.0f} MiB of EC-CSR images (cold cache)",
+                   "spmv_per_step": nshapes, "rotation_copies": copies},
+        "us_per_spmv": round(us_per_spmv, 3),
+        "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
+        "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "kernel": "ecspmv_kernel", "avg_launch_us": round(avg_launch_us, 3),
+                     "bytes_per_launch": round(byte_sum / n_ev),
+                     "timing": "HIP events on the launch stream around the whole timed region / launches (gaps included)"},
+    }
+
+    # ---- storage: EC-CSR bytes against CSR bytes ----------------------------------------------------------
+    nnz = sum(e["st"].nnz for e in mats[0])
+    img = sum(e["st"].image_bytes for e in mats[0])
+    need = sum(e["bytes"] for e in mats[0])
+    c32 = sum(e["st"].csr32_bytes for e in mats[0])
+    c16 = sum(e["st"].csr16_bytes for e in mats[0])
+    by_g = [int(sum(e["st"].nnz_by_g[k] for e in mats[0])) for k in range(5)]
+    out["storage"] = {"nnz_per_step": int(nnz), "eccsr_image_bytes": int(img), "eccsr_needed_bytes": int(need),
+                      "csr32_bytes": int(c32), "csr16_bytes": int(c16), "eccsr_over_csr32": round(img / c32, 4),
+                      "bytes_per_nnz": round(img / nnz, 4), "nnz_by_granularity_1_2_4_8_16": by_g,
+                      "pad_elements": int(sum(e["st"].pad_elements for e in mats[0])),
+                      "build_seconds_total": round(build_seconds, 2), "prep_seconds": round(t_prep, 1)}
+
+    detail = per_shape
+    out["per_shape_cold"] = per_shape
+
+    if not args.no_extras:
+        # hot cache: the same layer over and over (working set of one layer still exceeds L2)
+        for _ in range(3):
+            run_layer(mats[0])
+        torch.cuda.synchronize()
+        ev0.record(stream)
+        reps = max(10, args.steps // 2)
+        for _ in range(reps):
+            for e in mats[0][:1]:
+                e["A"].ecspmv_run(e["x"].data_ptr(), e["y"].data_ptr(), sh)
+        ev1.record(stream)
+        torch.cuda.synchronize()
+        ms = ev0.elapsed_time(ev1)
+        e0 = mats[0][0]
+        out["hot_cache"] = {"matrix": f'{e0["name"]} {e0["m"]}x{e0["n"]}', "us_per_spmv": round(ms * 1e3 / reps, 3),
+                            "gbps": round(e0["bytes"] * reps / (ms * 1e-3) / 1e9, 1)}
+
+        # streaming-read ceiling over the very same images, same rotation
+        chk = torch.zeros(1024, dtype=torch.int32, device="cuda")
+        for nwg in (256, 512, 1024):
+            for layer in mats[:2]:
+                for e in layer:
+                    E.ecspmv_stream_read(e["A"].d_image.data_ptr(), int(e["st"].image_bytes), chk.data_ptr(), nwg, sh)
+            torch.cuda.synchronize()
+            ev0.record(stream)
+            tot = 0
+            for s in range(min(args.steps, 4 * copies)):
+                for e in mats[s % copies]:
+                    E.ecspmv_stream_read(e["A"].d_image.data_ptr(), int(e["st"].image_bytes), chk.data_ptr(), nwg, sh)
+                    tot += int(e["st"].image_bytes)
+            ev1.record(stream)
+            torch.cuda.synchronize()
+            ms = ev0.elapsed_time(ev1)
+            out.setdefault("stream_read_ceiling_gbps", {})[f"{nwg}wg"] = round(tot / (ms * 1e-3) / 1e9, 1)
+
+        # plain CSR kernel on the same matrices (first two copies, rotation > 512 MB of CSR data)
+        csr_layers = []
+        for c in range(min(copies, 2)):
+            layer = []
+            for sid in range(nshapes):
+                W = keep_dense[sid][0] if c == 0 else gen.make_matrix(cfg, sid, seed=0, copy=c)
+                C = E.ecspmv_csr_build_dense(W)
+                D.csr_upload(C, stream=stream)
+                layer.append((C, mats[c][sid]))
+            csr_layers.append(layer)
+        for layer in csr_layers:
+            for C, e in layer:
+                C.ecspmv_csr_run(e["x"].data_ptr(), e["y"].data_ptr(), sh)
+        torch.cuda.synchronize()
+        ev0.record(stream)
+        reps = max(4, args.steps // 4)
+        for s in range(reps):
+            for C, e in csr_layers[s % len(csr_layers)]:
+                C.ecspmv_csr_run(e["x"].data_ptr(), e["y"].data_ptr(), sh)
+        ev1.record(stream)
+        torch.cuda.synchronize()
+        ms = ev0.elapsed_time(ev1)
+        csr_bytes = sum(int(e["st"].csr32_bytes) + 2 * e["n"] + 2 * e["m"] for _, e in csr_layers[0])
+        out["csr_kernel"] = {"us_per_spmv": round(ms * 1e3 / (reps * nshapes), 3),
+                             "gbps_of_csr32_bytes": round(csr_bytes * reps / (ms * 1e-3) / 1e9, 1),
+                             "speedup_eccsr_over_csr": round((ms * 1e3 / (reps * nshapes)) / us_per_spmv, 3)}
+
+    if not args.no_cpu_baseline:
+        from oracle import oracle as orc
+        times, cores = [], 1
+        for _ in range(3):
+            t = time.perf_counter()
+            for sid in range(nshapes):
+                W, x = keep_dense[sid]
+                _, _, cores = orc.spmv_oracle_threads(W, x)
+            times.append(time.perf_counter() - t)
+        tmed = float(np.median(times))
+        out["cpu_baseline"] = {"value": round(layer_bytes[0] / tmed / 1e9, 3), "unit": "GB/s", "cores": int(cores),
+                               "kind": "oracle",
+                               "sample": f"one step ({nshapes} dense-masked FP16 matrices of copy 0), FP64 oracle, "
+                                         f"median of 3 runs, {tmed * 1e3:.0f} ms per step; rate = the same EC-CSR+x+y "
+                                         "bytes / time",
+                               "us_per_spmv": round(tmed * 1e6 / nshapes, 1)}
+
+    if args.detail:
+        os.makedirs(os.path.dirname(os.path.abspath(args.detail)), exist_ok=True)
+        with open(args.detail, "w") as f:
+            json.dump({"summary": out, "per_shape": detail,
+                       "stats_copy0": [e["st"].as_dict() for e in mats[0]]}, f, indent=1)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -92,7 +92,14 @@ __device__ __forceinline__ float fma_h(uint32_t w_bits, float xf, float acc)
     return fmaf(half_bits_to_float(w_bits), xf, acc);
 }
 
-__device__ __forceinline__ uint4 load16(const uint8_t *p) { return *reinterpret_cast<const uint4 *>(p); }
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// 128-bit streaming load: every byte of the image is used once, so it is marked non-temporal
+__device__ __forceinline__ uint4 load16(const uint8_t *p)
+{
+    const u32x4 t = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
+    return make_uint4(t.x, t.y, t.z, t.w);
+}
 
 struct Ctx {
     const uint8_t *panel;      // global
