@@ -114,6 +114,10 @@ int ecspmv_block_sets(const ecspmv_matrix *A, int64_t *n_units, int64_t *n_rows,
 /* Size of the device image in bytes (a multiple of 256). */
 int ecspmv_device_bytes(const ecspmv_matrix *A, size_t *bytes);
 
+/* Copy the image into host memory (host_dst: host, >= ecspmv_device_bytes): for inspection, tests and caching.
+ * The layout is the one paper_2507_12205_amd/csrc/ecspmv_format.h describes. */
+int ecspmv_export_image(const ecspmv_matrix *A, void *host_dst, size_t bytes);
+
 /* Copy the image into d_buf (device, 256-byte aligned, >= ecspmv_device_bytes, allocated and owned by the
  * caller) on `stream`, and remember d_buf in the handle.  Returns after the copy has completed. */
 int ecspmv_upload(ecspmv_matrix *A, void *d_buf, size_t bytes, void *stream);

@@ -21,7 +21,7 @@ FLAG_NO_REORDER = 2
 
 EXPORTS = (
     "ecspmv_build_dense", "ecspmv_build_csr", "ecspmv_destroy", "ecspmv_stats", "ecspmv_decode",
-    "ecspmv_block_sets", "ecspmv_device_bytes", "ecspmv_upload", "ecspmv_run",
+    "ecspmv_block_sets", "ecspmv_device_bytes", "ecspmv_export_image", "ecspmv_upload", "ecspmv_run",
     "ecspmv_csr_build_dense", "ecspmv_csr_destroy", "ecspmv_csr_device_bytes", "ecspmv_csr_upload",
     "ecspmv_csr_run", "ecspmv_stream_read", "ecspmv_strerror", "ecspmv_last_hip_error",
 )
@@ -85,6 +85,7 @@ def lib() -> ctypes.CDLL:
     L.ecspmv_decode.argtypes = [c_void_p, POINTER(c_int64), c_void_p, c_void_p, c_void_p]
     L.ecspmv_block_sets.argtypes = [c_void_p, POINTER(c_int64), POINTER(c_int64), c_void_p, c_void_p, c_void_p]
     L.ecspmv_device_bytes.argtypes = [c_void_p, POINTER(c_size_t)]
+    L.ecspmv_export_image.argtypes = [c_void_p, c_void_p, c_size_t]
     L.ecspmv_upload.argtypes = [c_void_p, c_void_p, c_size_t, c_void_p]
     L.ecspmv_run.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p]
     L.ecspmv_csr_build_dense.argtypes = [c_void_p, c_int64, c_int64, c_int64, POINTER(c_void_p)]
@@ -177,6 +178,12 @@ class Matrix:
         b = c_size_t(0)
         _check(lib().ecspmv_device_bytes(self._h, byref(b)), "ecspmv_device_bytes")
         return int(b.value)
+
+    def ecspmv_export_image(self) -> np.ndarray:
+        n = self.ecspmv_device_bytes()
+        out = np.empty(n, dtype=np.uint8)
+        _check(lib().ecspmv_export_image(self._h, out.ctypes.data, n), "ecspmv_export_image")
+        return out
 
     def ecspmv_upload(self, d_ptr: int, nbytes: int, stream: int = 0, keepalive=None) -> None:
         _check(lib().ecspmv_upload(self._h, c_void_p(d_ptr), nbytes, c_void_p(stream)), "ecspmv_upload")

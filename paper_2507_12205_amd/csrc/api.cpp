@@ -190,6 +190,14 @@ int ecspmv_device_bytes(const ecspmv_matrix *A, size_t *bytes)
     return ECSPMV_OK;
 }
 
+int ecspmv_export_image(const ecspmv_matrix *A, void *host_dst, size_t bytes)
+{
+    if (!A || !host_dst) return ECSPMV_ERR_INVALID;
+    if (bytes < A->image.bytes.size()) return ECSPMV_ERR_TOO_SMALL;
+    std::memcpy(host_dst, A->image.bytes.data(), A->image.bytes.size());
+    return ECSPMV_OK;
+}
+
 int ecspmv_upload(ecspmv_matrix *A, void *d_buf, size_t bytes, void *stream)
 {
     if (!A || !d_buf || (reinterpret_cast<uintptr_t>(d_buf) & 255)) return ECSPMV_ERR_INVALID;

@@ -1,0 +1,100 @@
+"""Independent Python reading of the EC-CSR device image (layout as documented in csrc/ecspmv_format.h).
+
+Used by the tests only: it re-derives columns from bases and 8-bit deltas with the recurrence
+I_k = I_0 + sum_{i<=k} dI_i (paper Section 6.2) and undoes the value permutation of Section 6.3.2, without
+calling the library's own decoder.
+"""
+import numpy as np
+
+IMAGE_HEADER = 256
+PH = dict(ROW0=0, NROWS=1, NSLOTS=2, NRLANES=3, NRENTRIES=4, ROWSLOT_OFF=5, RCHUNK_OFF=6, RENTRY_OFF=7,
+          RD_OFF=8, RV_OFF=9, NUNITS=10, UTAB_OFF=14, BD_OFF=18, BV_OFF=22, PANEL_BYTES=26, META_BYTES=27)
+
+
+def image_header(img: np.ndarray) -> dict:
+    w = img[:48].view(np.uint32)
+    q = img[40:56].view(np.uint64)
+    return dict(magic=int(w[0]), version=int(w[1]), m=int(w[2]), n=int(w[3]), num_panels=int(w[4]),
+                threads_per_wg=int(w[5]), panel_stride=int(w[6]), meta_stride=int(w[7]), max_slots=int(w[8]),
+                lds_bytes=int(w[9]), image_bytes=int(q[0]), nnz=int(q[1]))
+
+
+def walk(img: np.ndarray):
+    """Yields dicts describing every unit of the image.
+
+    kind 'block': g, rows (g,), cols (64,), deltas (64,), base, values (64, g) uint16
+    kind 'lane':  row, cols (16,), deltas (16,), values (16,) uint16, first_of_row (bool)"""
+    ih = image_header(img)
+    for p in range(ih["num_panels"]):
+        P = img[IMAGE_HEADER + p * ih["panel_stride"]: IMAGE_HEADER + (p + 1) * ih["panel_stride"]]
+        hdr = P[:128].view(np.uint32)
+        row0, nrows = int(hdr[PH["ROW0"]]), int(hdr[PH["NROWS"]])
+        o = int(hdr[PH["ROWSLOT_OFF"]])
+        rowslot = P[o:o + 2 * (nrows + 1)].view(np.uint16).astype(np.int64)
+
+        def row_of_slot(s):
+            return int(np.searchsorted(rowslot, s, side="right")) - 1
+
+        for t in (3, 2, 1, 0):
+            g = 2 << t
+            nu = int(hdr[PH["NUNITS"] + t])
+            ut, bd, bv = int(hdr[PH["UTAB_OFF"] + t]), int(hdr[PH["BD_OFF"] + t]), int(hdr[PH["BV_OFF"] + t])
+            for u in range(nu):
+                ue = P[ut + 2 * (1 + g) * u: ut + 2 * (1 + g) * (u + 1)].view(np.uint16)
+                d = P[bd + 64 * u: bd + 64 * (u + 1)].astype(np.int64)
+                cols = int(ue[0]) + np.cumsum(d)                       # I_k = I_0 + sum of deltas
+                raw = P[bv + 128 * g * u: bv + 128 * g * (u + 1)].view(np.uint16)
+                flat = np.empty(64 * g, dtype=np.uint16)               # undo: k-th 8-half group of lane j at k*128 + 8j
+                for j in range(16):
+                    for k in range(g // 2):
+                        flat[4 * j * g + 8 * k: 4 * j * g + 8 * k + 8] = raw[k * 128 + 8 * j: k * 128 + 8 * j + 8]
+                yield dict(kind="block", panel=p, g=g, base=int(ue[0]), deltas=d, cols=cols,
+                           rows=np.array([row0 + row_of_slot(int(s)) for s in ue[1:]]),
+                           slots=ue[1:].astype(np.int64), values=flat.reshape(64, g))
+        nlanes = int(hdr[PH["NRLANES"]])
+        rc, re_, rd, rv = (int(hdr[PH[k]]) for k in ("RCHUNK_OFF", "RENTRY_OFF", "RD_OFF", "RV_OFF"))
+        prev_row = -1
+        for c in range((nlanes + 63) // 64):
+            ch = P[rc + 16 * c: rc + 16 * (c + 1)]
+            mask = int(ch[:8].view(np.uint64)[0])
+            entry0, nl = (int(v) for v in ch[8:16].view(np.uint32))
+            assert nl == min(64, nlanes - 64 * c) and (mask & 1)
+            excl = 0
+            for l in range(nl):
+                seg = bin(mask & ((2 << l) - 1)).count("1") - 1
+                e = P[re_ + 8 * (entry0 + seg): re_ + 8 * (entry0 + seg + 1)]
+                cc = int(e[:4].view(np.int32)[0])
+                slot, row_local = (int(v) for v in e[4:8].view(np.uint16))
+                d = P[rd + 1024 * c + 16 * l: rd + 1024 * c + 16 * (l + 1)].astype(np.int64)
+                v0 = P[rv + 2048 * c + 16 * l: rv + 2048 * c + 16 * (l + 1)].view(np.uint16)
+                v1 = P[rv + 2048 * c + 16 * nl + 16 * l: rv + 2048 * c + 16 * nl + 16 * (l + 1)].view(np.uint16)
+                cols = cc + excl + np.cumsum(d)
+                excl += int(d.sum())
+                assert row_of_slot(slot) == row_local
+                yield dict(kind="lane", panel=p, row=row0 + row_local, deltas=d, cols=cols,
+                           values=np.concatenate([v0, v1]), first_of_row=(row_local != prev_row), slot=slot,
+                           head=bool((mask >> l) & 1))
+                prev_row = row_local
+
+
+def triples(img: np.ndarray):
+    """(rows, cols, value bits) of every stored entry (padding zeros dropped), sorted by (row, col)."""
+    r, c, v = [], [], []
+    for u in walk(img):
+        if u["kind"] == "block":
+            for k in range(u["g"]):
+                r.append(np.full(64, u["rows"][k]))
+                c.append(u["cols"])
+                v.append(u["values"][:, k])
+        else:
+            r.append(np.full(16, u["row"]))
+            c.append(u["cols"])
+            v.append(u["values"])
+    if not r:
+        z = np.zeros(0, dtype=np.int64)
+        return z, z, z.astype(np.uint16)
+    r, c, v = np.concatenate(r), np.concatenate(c), np.concatenate(v)
+    keep = (v & 0x7FFF) != 0
+    r, c, v = r[keep], c[keep], v[keep]
+    o = np.lexsort((c, r))
+    return r[o], c[o], v[o]
