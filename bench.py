@@ -41,6 +41,9 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip hot-cache, CSR and streaming-read legs")
     ap.add_argument("--detail", type=str, default="", help="write per-shape details to this JSON file")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 256 MiB device-to-device copy three times (known traffic, for scaling "
+                         "rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     return ap.parse_args()
 
 
@@ -160,6 +163,14 @@ def main():
     achieved = value
     byte_sum, n_ev = moved, nlaunch
 
+    # HBM traffic per launch as counted by rocprofv3 (FETCH_SIZE + WRITE_SIZE runs, see profiles/): measured in
+    # separate profiler runs of this same command, so it is read from the committed summary, not sampled here
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "ecspmv_kernel_config3_hbm_traffic.json")
+    if args.config == 3 and not (args.max_granularity or args.panels or args.threads_per_wg) and os.path.exists(tpath):
+        with open(tpath) as f:
+            traffic = json.load(f).get("traffic_bytes_per_launch")
+
     out = {
         "metric": "effective HBM GB/s of cold-cache EC-CSR SpMV (EC-CSR bytes + x + y per SpMV / time)",
         "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -173,7 +184,7 @@ def main():
         "us_per_spmv": round(us_per_spmv, 3),
         "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
                      "kernel": "ecspmv_kernel", "avg_launch_us": round(avg_launch_us, 3),
                      "bytes_per_launch": round(byte_sum / n_ev),
                      "timing": "HIP events on the launch stream around the whole timed region / launches (gaps included)"},
@@ -256,6 +267,14 @@ def main():
         out["csr_kernel"] = {"us_per_spmv": round(ms * 1e3 / (reps * nshapes), 3),
                              "gbps_of_csr32_bytes": round(csr_bytes * reps / (ms * 1e-3) / 1e9, 1),
                              "speedup_eccsr_over_csr": round((ms * 1e3 / (reps * nshapes)) / us_per_spmv, 3)}
+
+    if args.calibrate_copy:
+        src = torch.randint(0, 127, (256 << 20,), dtype=torch.int8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        out["calibration_copy_bytes"] = int(src.numel())
 
     if not args.no_cpu_baseline:
         from oracle import oracle as orc
