@@ -38,6 +38,10 @@ def parse_args():
     ap.add_argument("--max-granularity", type=int, default=0)
     ap.add_argument("--panels", type=int, default=0)
     ap.add_argument("--threads-per-wg", type=int, default=0)
+    ap.add_argument("--launch", choices=["single", "groups", "all"], default="single",
+                    help="how the SpMVs of a step are submitted in the timed region: one launch each (single), "
+                         "one launch per group of projections that are independent in a decoder layer (groups: "
+                         "q+k+v, o, gate+up, down), or one launch for the whole step (all)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip hot-cache, CSR and streaming-read legs")
     ap.add_argument("--detail", type=str, default="", help="write per-shape details to this JSON file")
@@ -112,9 +116,40 @@ def main():
     image_total = sum(e["st"].image_bytes for layer in mats for e in layer)
     layer_bytes = [sum(e["bytes"] for e in layer) for layer in mats]
 
-    def run_layer(layer):
-        for e in layer:
-            e["A"].ecspmv_run(e["x"].data_ptr(), e["y"].data_ptr(), sh)
+    def group_of(names):
+        # projections of a decoder layer that do not depend on one another share a launch
+        groups, cur, key = [], [], None
+        fam = {"q": "qkv", "k": "qkv", "v": "qkv", "gate": "gu", "up": "gu"}
+        for i, nm in enumerate(names):
+            kf = fam.get(nm, f"solo{i}")
+            if cur and kf != key:
+                groups.append(cur)
+                cur = []
+            cur.append(i)
+            key = kf
+        if cur:
+            groups.append(cur)
+        return groups
+
+    def batches_for(layer, mode):
+        names = [e["name"] for e in layer]
+        if mode == "all":
+            groups = [list(range(len(layer)))]
+        else:
+            groups = group_of(names)
+        return [E.Batch([layer[i]["A"] for i in g], [layer[i]["x"].data_ptr() for i in g],
+                        [layer[i]["y"].data_ptr() for i in g]) for g in groups]
+
+    batched = {mode: [batches_for(layer, mode) for layer in mats] for mode in ("groups", "all")}
+
+    def run_layer(layer, mode=None):
+        mode = mode or args.launch
+        if mode == "single":
+            for e in layer:
+                e["A"].ecspmv_run(e["x"].data_ptr(), e["y"].data_ptr(), sh)
+        else:
+            for b in batched[mode][mats.index(layer)]:
+                b.ecspmv_run_batch(sh)
 
     # ---- timed region: K steps, cold cache (rotation) ---------------------------------------------------
     for w in range(args.warmup):
@@ -205,6 +240,27 @@ def main():
 
     detail = per_shape
     out["per_shape_cold"] = per_shape
+
+    # the same steps submitted with fewer launches (cold rotation, same events)
+    out["launch_mode"] = args.launch
+    out["launches_per_step"] = {"single": nshapes, "groups": len(batched["groups"][0]), "all": 1}[args.launch]
+    alt = {}
+    for mode in ("single", "groups", "all"):
+        for w in range(min(args.warmup, copies)):
+            run_layer(mats[w % copies], mode)
+        torch.cuda.synchronize()
+        ev0.record(stream)
+        for s_ in range(args.steps):
+            run_layer(mats[(args.warmup + s_) % copies], mode)
+        ev1.record(stream)
+        torch.cuda.synchronize()
+        ms = ev0.elapsed_time(ev1)
+        nl = {"single": nshapes, "groups": len(batched["groups"][0]), "all": 1}[mode]
+        alt[mode] = {"launches_per_step": nl, "us_per_step": round(ms * 1e3 / args.steps, 3),
+                     "us_per_spmv": round(ms * 1e3 / (args.steps * nshapes), 3),
+                     "gbps": round(moved / (ms * 1e-3) / 1e9, 1),
+                     "pct_of_hbm_peak": round(100.0 * moved / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 2)}
+    out["by_launch_mode"] = alt
 
     if not args.no_extras:
         # hot cache: the same layer over and over (working set of one layer still exceeds L2)

@@ -6,5 +6,5 @@ PyTorch own the device buffers and streams.
 from . import binding  # noqa: F401
 from .binding import (  # noqa: F401
     EcspmvError, Matrix, CsrMatrix, make_opts, ecspmv_build_dense, ecspmv_build_csr,
-    ecspmv_csr_build_dense, ecspmv_stream_read,
+    ecspmv_csr_build_dense, ecspmv_stream_read, ecspmv_run_batch, Batch,
 )

@@ -21,7 +21,7 @@ FLAG_NO_REORDER = 2
 
 EXPORTS = (
     "ecspmv_build_dense", "ecspmv_build_csr", "ecspmv_destroy", "ecspmv_stats", "ecspmv_decode",
-    "ecspmv_block_sets", "ecspmv_device_bytes", "ecspmv_export_image", "ecspmv_upload", "ecspmv_run",
+    "ecspmv_block_sets", "ecspmv_device_bytes", "ecspmv_export_image", "ecspmv_upload", "ecspmv_run", "ecspmv_run_batch",
     "ecspmv_csr_build_dense", "ecspmv_csr_destroy", "ecspmv_csr_device_bytes", "ecspmv_csr_upload",
     "ecspmv_csr_run", "ecspmv_stream_read", "ecspmv_strerror", "ecspmv_last_hip_error",
 )
@@ -88,6 +88,7 @@ def lib() -> ctypes.CDLL:
     L.ecspmv_export_image.argtypes = [c_void_p, c_void_p, c_size_t]
     L.ecspmv_upload.argtypes = [c_void_p, c_void_p, c_size_t, c_void_p]
     L.ecspmv_run.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p]
+    L.ecspmv_run_batch.argtypes = [c_void_p, c_void_p, c_void_p, c_int32, c_void_p]
     L.ecspmv_csr_build_dense.argtypes = [c_void_p, c_int64, c_int64, c_int64, POINTER(c_void_p)]
     L.ecspmv_csr_destroy.argtypes = [c_void_p]
     L.ecspmv_csr_destroy.restype = None
@@ -191,6 +192,26 @@ class Matrix:
 
     def ecspmv_run(self, d_x: int, d_y: int, stream: int = 0) -> None:
         _check(lib().ecspmv_run(self._h, c_void_p(d_x), c_void_p(d_y), c_void_p(stream)), "ecspmv_run")
+
+
+class Batch:
+    """Pre-marshalled argument arrays of ecspmv_run_batch (handles, x pointers, y pointers)."""
+
+    def __init__(self, mats, d_xs, d_ys):
+        assert len(mats) == len(d_xs) == len(d_ys) and len(mats) > 0
+        n = len(mats)
+        self.count = n
+        self._mats = list(mats)                     # keep the handles alive
+        self._h = (c_void_p * n)(*[m._h.value for m in mats])
+        self._x = (c_void_p * n)(*[int(p) for p in d_xs])
+        self._y = (c_void_p * n)(*[int(p) for p in d_ys])
+
+    def ecspmv_run_batch(self, stream: int = 0) -> None:
+        _check(lib().ecspmv_run_batch(self._h, self._x, self._y, self.count, c_void_p(stream)), "ecspmv_run_batch")
+
+
+def ecspmv_run_batch(mats, d_xs, d_ys, stream: int = 0) -> None:
+    Batch(mats, d_xs, d_ys).ecspmv_run_batch(stream)
 
 
 def ecspmv_build_dense(W: np.ndarray, opts: BuildOpts | None = None) -> Matrix:

@@ -1,4 +1,5 @@
 // C ABI of the library (see include/ecspmv.h): argument checks, option defaults, handle bookkeeping.
+#include <algorithm>
 #include <cstring>
 #include <new>
 #include <vector>
@@ -54,7 +55,7 @@ int parse_opts(const ecspmv_build_opts *o, ecs::BuildParams &bp)
     bp.max_rounds = opts.max_rounds ? opts.max_rounds : 64;
     bp.num_panels = opts.num_panels;
     bp.num_threads = opts.num_threads;
-    const int t = opts.threads_per_wg ? opts.threads_per_wg : 1024;
+    const int t = opts.threads_per_wg ? opts.threads_per_wg : 512;
     if (t < 64 || t > 1024 || t % 64) return ECSPMV_ERR_INVALID;
     bp.threads_per_wg = t;
     bp.global_matching = (opts.flags & ECSPMV_FLAG_GLOBAL_MATCHING) != 0;
@@ -212,15 +213,50 @@ int ecspmv_upload(ecspmv_matrix *A, void *d_buf, size_t bytes, void *stream)
     return ECSPMV_OK;
 }
 
+int ecspmv_run_batch(const ecspmv_matrix *const *As, const void *const *d_xs, void *const *d_ys, int32_t count,
+                     void *stream)
+{
+    if (!As || !d_xs || !d_ys || count <= 0) return ECSPMV_ERR_INVALID;
+    for (int32_t i = 0; i < count; ++i) {
+        if (!As[i] || !d_xs[i] || !d_ys[i]) return ECSPMV_ERR_INVALID;
+        if ((reinterpret_cast<uintptr_t>(d_xs[i]) & 1) || (reinterpret_cast<uintptr_t>(d_ys[i]) & 1))
+            return ECSPMV_ERR_INVALID;
+        if (!As[i]->d_image) return ECSPMV_ERR_NOT_UPLOADED;
+        if (As[i]->image.threads_per_wg != As[0]->image.threads_per_wg) return ECSPMV_ERR_INVALID;
+    }
+    std::vector<int32_t> order((size_t)count);
+    for (int32_t i = 0; i < count; ++i) order[(size_t)i] = i;
+    for (int32_t base = 0; base < count; base += ECS_MAX_BATCH) {       // one launch per ECS_MAX_BATCH matrices
+        const int32_t nb = count - base < ECS_MAX_BATCH ? count - base : ECS_MAX_BATCH;
+        ecs::EcsBatch b;
+        std::memset(&b, 0, sizeof(b));
+        b.count = (uint32_t)nb;
+        uint32_t blocks = 0, lds = 0, mask = 0;
+        for (int32_t i = 0; i < nb; ++i) {
+            const int32_t src = order[(size_t)(base + i)];
+            const ecs::Image &im = As[src]->image;
+            ecs::EcsBatchItem &it = b.item[i];
+            it.image = static_cast<const uint8_t *>(As[src]->d_image);
+            it.x = static_cast<const uint16_t *>(d_xs[src]);
+            it.y = static_cast<uint16_t *>(d_ys[src]);
+            it.n = (uint32_t)im.n;
+            it.panel_stride = im.panel_stride;
+            it.meta_stride = im.meta_stride;
+            it.x_bytes = ((uint32_t)im.n * 2u + 15u) / 16u * 16u;
+            blocks += (uint32_t)im.num_panels;
+            it.block_end = blocks;
+            lds = im.lds_bytes > lds ? im.lds_bytes : lds;
+            mask |= im.type_mask;
+        }
+        int s = hip_status(ecs::launch_ecspmv(b, (uint32_t)As[order[(size_t)base]]->image.threads_per_wg, lds, mask, stream));
+        if (s) return s;
+    }
+    return ECSPMV_OK;
+}
+
 int ecspmv_run(const ecspmv_matrix *A, const void *d_x, void *d_y, void *stream)
 {
-    if (!A || !d_x || !d_y) return ECSPMV_ERR_INVALID;
-    if ((reinterpret_cast<uintptr_t>(d_x) & 1) || (reinterpret_cast<uintptr_t>(d_y) & 1)) return ECSPMV_ERR_INVALID;
-    if (!A->d_image) return ECSPMV_ERR_NOT_UPLOADED;
-    const ecs::Image &im = A->image;
-    return hip_status(ecs::launch_ecspmv(A->d_image, d_x, d_y, (uint32_t)im.n, (uint32_t)im.num_panels,
-                                         (uint32_t)im.threads_per_wg, im.panel_stride, im.meta_stride, im.lds_bytes,
-                                         stream));
+    return ecspmv_run_batch(&A, &d_x, &d_y, 1, stream);
 }
 
 int ecspmv_csr_build_dense(const uint16_t *W, int64_t m, int64_t n, int64_t ld, ecspmv_csr **out)

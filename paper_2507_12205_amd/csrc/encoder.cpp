@@ -589,7 +589,8 @@ int build_image(const Csr &A, const BuildParams &bp, Image &out)
         slots = std::max(slots, im.nslots);
     }
     meta = align_up(meta, 16);
-    const uint64_t total = ECS_IMAGE_HEADER + (uint64_t)stride * (uint64_t)P;
+    // 4 KB of zeros after the last panel: loads that stand in for missing chunks may run past a short last panel
+    const uint64_t total = ECS_IMAGE_HEADER + (uint64_t)stride * (uint64_t)P + 4096u;
     if (total > 0xFFFFFFFF00ull) return -2;
     out.bytes.assign((size_t)total, 0);
     out.m = m;
@@ -634,6 +635,9 @@ int build_image(const Csr &A, const BuildParams &bp, Image &out)
         }
         for (int k = 0; k < 9; ++k) st.delta_hist[k] += im.delta_hist[k];
     }
+    out.type_mask = 0;
+    for (int t = 0; t < ECS_NUM_BTYPES; ++t)
+        if (st.units_by_g[t + 1] > 0) out.type_mask |= 1u << t;
     st.meta_bytes += ECS_IMAGE_HEADER;
     st.slack_bytes = st.image_bytes - st.value_bytes - st.delta_bytes - st.meta_bytes;
     for (int k = 0; k < 5; ++k) st.x_access_cost += (double)st.nnz_by_g[k] / (double)(1 << k);

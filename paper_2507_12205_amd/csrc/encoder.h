@@ -22,7 +22,7 @@ struct BuildParams {
     int max_rounds = 64;
     int num_panels = 0;
     int num_threads = 0;
-    int threads_per_wg = 1024;
+    int threads_per_wg = 512;
     bool global_matching = false;
     bool reorder = true;
 };
@@ -32,6 +32,7 @@ struct Image {
     int64_t m = 0, n = 0, nnz = 0;
     int num_panels = 0, threads_per_wg = 1024;
     uint32_t panel_stride = 0, meta_stride = 0, max_slots = 0, lds_bytes = 0;
+    uint32_t type_mask = 0;   // bit t set: some panel holds units of granularity 2 << t
     ecspmv_stats_t stats;
 };
 

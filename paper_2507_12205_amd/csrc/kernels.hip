@@ -101,42 +101,48 @@ __device__ __forceinline__ uint4 load16(const uint8_t *p)
     return make_uint4(t.x, t.y, t.z, t.w);
 }
 
+__device__ __forceinline__ uint32_t load4(const uint8_t *p)
+{
+    return __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(p));
+}
+
 struct Ctx {
     const uint8_t *panel;      // global
     const uint16_t *xs;        // LDS: x as FP16 bits
     const uint8_t *meta;       // LDS copy of the panel's meta region
     float *slots;              // LDS partial sums
-    int wave, lane, nwaves;
+    uint32_t wave, lane, nwaves;
 };
 
-// ---- g >= 2 block sets: a DPP row of 16 lanes takes one unit (64 columns), 4 columns per lane.
+// ---- g >= 2 block sets: a DPP row of 16 lanes takes one unit (64 columns), 4 columns per lane; a wavefront
+// takes a chunk of 4 consecutive units.
 template <int G>
 struct UnitRegs {
     uint32_t d;            // 4 delta bytes
     uint4 v[G / 2];        // 4 * G FP16 values of this lane
 };
 
+// Unconditional: DPP rows beyond the last unit of the set re-read that last unit (and ignore it), so that the
+// number of loads in flight never depends on data and waits can name exact counts.
 template <int G>
-__device__ __forceinline__ void load_unit(const Ctx &c, const uint8_t *bd, const uint8_t *bv, uint32_t u, uint32_t nu,
+__device__ __forceinline__ void load_unit(const Ctx &c, uint32_t bd_off, uint32_t bv_off, uint32_t u, uint32_t nu,
                                           UnitRegs<G> &r)
 {
-    const int j = c.lane & 15;
-    if (u < nu) {
-        r.d = *reinterpret_cast<const uint32_t *>(bd + 64u * u + 4u * j);
+    const uint32_t j = c.lane & 15;
+    const uint32_t uu = min(u, nu - 1u);
+    r.d = load4(c.panel + bd_off + 64u * uu + 4u * j);
+    const uint8_t *pv = c.panel + bv_off + (128u * G) * uu + 16u * j;
 #pragma unroll
-        for (int k = 0; k < G / 2; ++k) r.v[k] = load16(bv + (size_t)(128u * G) * u + 256u * k + 16u * j);
-    } else {
-        r.d = 0;
-#pragma unroll
-        for (int k = 0; k < G / 2; ++k) r.v[k] = make_uint4(0, 0, 0, 0);
-    }
+    for (int k = 0; k < G / 2; ++k) r.v[k] = load16(pv + 256u * k);
 }
 
 template <int G>
 __device__ __forceinline__ void compute_unit(const Ctx &c, const uint16_t *utab, uint32_t u, uint32_t nu,
                                              const UnitRegs<G> &r)
 {
-    const int j = c.lane & 15;
+    const uint32_t j = c.lane & 15;
+    const bool active = u < nu;
+    const uint32_t uu = min(u, nu - 1u);
     // delta decode: local prefix over the lane's 4 columns, exclusive scan over the 16 lanes, unit base
     uint32_t rel[4];
     rel[0] = r.d & 0xFF;
@@ -144,19 +150,18 @@ __device__ __forceinline__ void compute_unit(const Ctx &c, const uint16_t *utab,
     rel[2] = rel[1] + ((r.d >> 16) & 0xFF);
     rel[3] = rel[2] + (r.d >> 24);
     const int incl = row16_incl_scan((int)rel[3]);
-    const bool active = u < nu;
-    const uint16_t *ue = utab + (active ? u : 0) * (1 + G);
-    const uint32_t start = (active ? (uint32_t)ue[0] : 0u) + (uint32_t)incl - rel[3];
+    const uint16_t *ue = utab + uu * (1 + G);
+    const uint32_t start = (uint32_t)ue[0] + (uint32_t)incl - rel[3];
     float xv[4];
 #pragma unroll
-    for (int k = 0; k < 4; ++k) xv[k] = active ? half_bits_to_float(c.xs[start + rel[k]]) : 0.0f;
+    for (int k = 0; k < 4; ++k) xv[k] = half_bits_to_float(c.xs[start + rel[k]]);
     float acc[G];
 #pragma unroll
     for (int q = 0; q < G; ++q) acc[q] = 0.0f;
-    const uint32_t *w = reinterpret_cast<const uint32_t *>(r.v);   // 2 * G dwords, 2 halfs each
 #pragma unroll
     for (int f = 0; f < 4 * G; ++f) {                              // f = column * G + row
-        const uint32_t word = w[f >> 1];
+        const uint4 q = r.v[f >> 3];
+        const uint32_t word = ((f >> 1) & 3) == 0 ? q.x : ((f >> 1) & 3) == 1 ? q.y : ((f >> 1) & 3) == 2 ? q.z : q.w;
         const uint32_t hb = (f & 1) ? (word >> 16) : (word & 0xFFFF);
         acc[f % G] = fma_h(hb, xv[f / G], acc[f % G]);
     }
@@ -164,33 +169,56 @@ __device__ __forceinline__ void compute_unit(const Ctx &c, const uint16_t *utab,
     for (int q = 0; q < G; ++q) acc[q] = row16_allreduce(acc[q]);
     float out = acc[0];
 #pragma unroll
-    for (int q = 1; q < G; ++q) out = (j == q) ? acc[q] : out;
-    if (active && j < G) c.slots[ue[1 + j]] = out;
+    for (int q = 1; q < G; ++q) out = (j == (uint32_t)q) ? acc[q] : out;
+    if (active && j < (uint32_t)G) c.slots[ue[1 + j]] = out;
 }
 
+// A set's chunks c0, c0 + W, c0 + 2W, ... belong to this wavefront.  Two register buffers A and B alternate:
+// both are requested before anything is computed, and each is refilled right after it has been consumed, so a
+// wavefront always has its next two chunks on the way (the double buffering of Section 7, without copies).
 template <int G>
-__device__ __forceinline__ void run_block_set(const Ctx &c, const uint32_t *hdr, int t)
-{
-    const uint32_t nu = hdr[PH_NUNITS + t];
-    if (nu == 0) return;
-    const uint8_t *bd = c.panel + hdr[PH_BD_OFF + t];
-    const uint8_t *bv = c.panel + hdr[PH_BV_OFF + t];
-    const uint16_t *utab = reinterpret_cast<const uint16_t *>(c.meta + hdr[PH_UTAB_OFF + t]);
-    const uint32_t step = 4u * c.nwaves;
-    uint32_t u0 = 4u * c.wave;                      // wave-uniform
-    if (u0 >= nu) return;
-    UnitRegs<G> cur, nxt;
-    load_unit<G>(c, bd, bv, u0 + (c.lane >> 4), nu, cur);
-    while (true) {
-        const uint32_t n0 = u0 + step;
-        const bool more = n0 < nu;
-        if (more) load_unit<G>(c, bd, bv, n0 + (c.lane >> 4), nu, nxt);   // prefetch while computing
-        compute_unit<G>(c, utab, u0 + (c.lane >> 4), nu, cur);
-        if (!more) break;
-        cur = nxt;
-        u0 = n0;
+struct BlockSet {
+    UnitRegs<G> A, B;
+    uint32_t nu, n, c0, bd_off, bv_off;
+    const uint16_t *utab;
+
+    __device__ __forceinline__ uint32_t unit_of(const Ctx &c, uint32_t i) const
+    {
+        return 4u * (c0 + i * c.nwaves) + (c.lane >> 4);
     }
-}
+    __device__ __forceinline__ void prologue(const Ctx &c, const uint32_t *hdr, int t)
+    {
+        nu = hdr[PH_NUNITS + t];
+        bd_off = hdr[PH_BD_OFF + t];
+        bv_off = hdr[PH_BV_OFF + t];
+        utab = reinterpret_cast<const uint16_t *>(c.meta + hdr[PH_UTAB_OFF + t]);
+        const uint32_t nch = (nu + 3u) >> 2;
+        c0 = c.wave;
+        n = nch > c0 ? (nch - c0 + c.nwaves - 1u) / c.nwaves : 0u;
+        // Both buffers are requested whether or not this wavefront has that many chunks (a missing chunk re-reads
+        // the set's last unit, an empty set reads the panel header): every wavefront then enters the loops below
+        // with the same loads in flight, which keeps the wait counts exact.
+        const uint32_t ebd = nu ? bd_off : 0u, ebv = nu ? bv_off : 0u, enu = nu ? nu : 1u;
+        load_unit<G>(c, ebd, ebv, unit_of(c, 0), enu, A);
+        load_unit<G>(c, ebd, ebv, unit_of(c, 1), enu, B);
+    }
+    __device__ __forceinline__ void run(const Ctx &c)
+    {
+        uint32_t i = 0;
+        for (; i + 3 < n; i += 2) {                    // chunks i + 2 and i + 3 exist: the refills are unconditional
+            compute_unit<G>(c, utab, unit_of(c, i), nu, A);
+            load_unit<G>(c, bd_off, bv_off, unit_of(c, i + 2), nu, A);
+            compute_unit<G>(c, utab, unit_of(c, i + 1), nu, B);
+            load_unit<G>(c, bd_off, bv_off, unit_of(c, i + 3), nu, B);
+        }
+        if (i < n) {
+            compute_unit<G>(c, utab, unit_of(c, i), nu, A);
+            if (i + 2 < n) load_unit<G>(c, bd_off, bv_off, unit_of(c, i + 2), nu, A);
+        }
+        if (i + 1 < n) compute_unit<G>(c, utab, unit_of(c, i + 1), nu, B);
+        if (i + 2 < n) compute_unit<G>(c, utab, unit_of(c, i + 2), nu, A);
+    }
+};
 
 // ---- residual (1-grained) set: a wavefront takes a chunk of 64 lane units, 16 elements per lane.
 struct ChunkRegs {
@@ -198,29 +226,25 @@ struct ChunkRegs {
     uint4 v0, v1; // 16 FP16 values
 };
 
-__device__ __forceinline__ void load_chunk(const Ctx &c, const uint8_t *rd, const uint8_t *rv, uint32_t ch, uint32_t nlanes,
+__device__ __forceinline__ void load_chunk(const Ctx &c, uint32_t rd_off, uint32_t rv_off, uint32_t ch, uint32_t nlanes,
                                            ChunkRegs &r)
 {
     const uint32_t nl = min(64u, nlanes - 64u * ch);
-    if ((uint32_t)c.lane < nl) {
-        r.d = load16(rd + 1024u * ch + 16u * c.lane);
-        r.v0 = load16(rv + 2048u * ch + 16u * c.lane);
-        r.v1 = load16(rv + 2048u * ch + 16u * nl + 16u * c.lane);
-    } else {
-        r.d = make_uint4(0, 0, 0, 0);
-        r.v0 = make_uint4(0, 0, 0, 0);
-        r.v1 = make_uint4(0, 0, 0, 0);
-    }
+    const uint32_t ll = min(c.lane, nl - 1u);           // lanes beyond the chunk's end re-read its last lane unit
+    r.d = load16(c.panel + rd_off + 1024u * ch + 16u * ll);
+    const uint8_t *pv = c.panel + rv_off + 2048u * ch + 16u * ll;
+    r.v0 = load16(pv);
+    r.v1 = load16(pv + 16u * nl);
 }
 
 __device__ __forceinline__ void compute_chunk(const Ctx &c, const EcsRChunk *rch, const EcsREntry *ren, uint32_t ch,
                                               uint32_t nlanes, const ChunkRegs &r)
 {
     const uint32_t nl = min(64u, nlanes - 64u * ch);
-    const bool active = (uint32_t)c.lane < nl;
+    const bool active = c.lane < nl;
     // lane-local inclusive prefix of the 16 deltas
     uint32_t rel[16];
-    const uint32_t dw[4] = {r.d.x, r.d.y, r.d.z, r.d.w};
+    const uint32_t dw[4] = {active ? r.d.x : 0u, active ? r.d.y : 0u, active ? r.d.z : 0u, active ? r.d.w : 0u};
     uint32_t run = 0;
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
@@ -235,49 +259,76 @@ __device__ __forceinline__ void compute_chunk(const Ctx &c, const EcsRChunk *rch
     const EcsREntry e = ren[rch[ch].entry0 + seg];
     const int start = e.c + incl - (int)run;
     float acc = 0.0f;
-    if (active) {
-        const uint32_t vw[8] = {r.v0.x, r.v0.y, r.v0.z, r.v0.w, r.v1.x, r.v1.y, r.v1.z, r.v1.w};
+    const uint32_t vw[8] = {r.v0.x, r.v0.y, r.v0.z, r.v0.w, r.v1.x, r.v1.y, r.v1.z, r.v1.w};
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const uint32_t word = vw[i >> 1];
-            const uint32_t hb = (i & 1) ? (word >> 16) : (word & 0xFFFF);
-            acc = fma_h(hb, half_bits_to_float(c.xs[start + (int)rel[i]]), acc);
-        }
+    for (int i = 0; i < 16; ++i) {
+        const uint32_t word = vw[i >> 1];
+        const uint32_t hb = (i & 1) ? (word >> 16) : (word & 0xFFFF);
+        acc = fma_h(hb, half_bits_to_float(c.xs[start + (int)rel[i]]), acc);
     }
+    acc = active ? acc : 0.0f;
     // segmented wavefront reduction: the last lane of every row segment holds its sum
     const int head = (int)((mask >> c.lane) & 1ull);
     const float seg_sum = wave64_seg_incl_scan(acc, head);
-    const bool is_end = active && ((uint32_t)c.lane + 1 == nl || ((mask >> (c.lane + 1)) & 1ull));
+    const bool is_end = active && (c.lane + 1 == nl || ((mask >> (c.lane + 1)) & 1ull));
     if (is_end) c.slots[e.slot] = seg_sum;
 }
 
-__device__ __forceinline__ void run_residual(const Ctx &c, const uint32_t *hdr)
-{
-    const uint32_t nlanes = hdr[PH_NRLANES];
-    const uint32_t nch = (nlanes + 63u) >> 6;
-    uint32_t ch = c.wave;
-    if (ch >= nch) return;
-    const uint8_t *rd = c.panel + hdr[PH_RD_OFF];
-    const uint8_t *rv = c.panel + hdr[PH_RV_OFF];
-    const EcsRChunk *rch = reinterpret_cast<const EcsRChunk *>(c.meta + hdr[PH_RCHUNK_OFF]);
-    const EcsREntry *ren = reinterpret_cast<const EcsREntry *>(c.meta + hdr[PH_RENTRY_OFF]);
-    ChunkRegs cur, nxt;
-    load_chunk(c, rd, rv, ch, nlanes, cur);
-    while (true) {
-        const uint32_t nc = ch + c.nwaves;
-        const bool more = nc < nch;
-        if (more) load_chunk(c, rd, rv, nc, nlanes, nxt);
-        compute_chunk(c, rch, ren, ch, nlanes, cur);
-        if (!more) break;
-        cur = nxt;
-        ch = nc;
-    }
-}
+struct ResidualSet {
+    ChunkRegs A, B;
+    uint32_t nlanes, n, c0, rd_off, rv_off;
+    const EcsRChunk *rch;
+    const EcsREntry *ren;
 
-__global__ __launch_bounds__(1024) void ecspmv_kernel(const uint8_t *__restrict__ image, const uint16_t *__restrict__ x,
-                                                      uint16_t *__restrict__ y, uint32_t n, uint32_t panel_stride,
-                                                      uint32_t meta_stride, uint32_t x_bytes)
+    __device__ __forceinline__ uint32_t chunk_of(const Ctx &c, uint32_t i) const { return c0 + i * c.nwaves; }
+    __device__ __forceinline__ void prologue(const Ctx &c, const uint32_t *hdr)
+    {
+        nlanes = hdr[PH_NRLANES];
+        rd_off = hdr[PH_RD_OFF];
+        rv_off = hdr[PH_RV_OFF];
+        rch = reinterpret_cast<const EcsRChunk *>(c.meta + hdr[PH_RCHUNK_OFF]);
+        ren = reinterpret_cast<const EcsREntry *>(c.meta + hdr[PH_RENTRY_OFF]);
+        const uint32_t nch = (nlanes + 63u) >> 6;
+        c0 = c.wave;
+        n = nch > c0 ? (nch - c0 + c.nwaves - 1u) / c.nwaves : 0u;
+        // unconditional, like the block sets: a missing chunk re-reads the last one, an empty set the panel header
+        const uint32_t erd = nch ? rd_off : 0u, erv = nch ? rv_off : 0u, enl = nch ? nlanes : 1u, last = nch ? nch - 1u : 0u;
+        load_chunk(c, erd, erv, min(chunk_of(c, 0), last), enl, A);
+        load_chunk(c, erd, erv, min(chunk_of(c, 1), last), enl, B);
+    }
+    __device__ __forceinline__ void run(const Ctx &c)
+    {
+        uint32_t i = 0;
+        for (; i + 3 < n; i += 2) {
+            compute_chunk(c, rch, ren, chunk_of(c, i), nlanes, A);
+            load_chunk(c, rd_off, rv_off, chunk_of(c, i + 2), nlanes, A);
+            compute_chunk(c, rch, ren, chunk_of(c, i + 1), nlanes, B);
+            load_chunk(c, rd_off, rv_off, chunk_of(c, i + 3), nlanes, B);
+        }
+        if (i < n) {
+            compute_chunk(c, rch, ren, chunk_of(c, i), nlanes, A);
+            if (i + 2 < n) load_chunk(c, rd_off, rv_off, chunk_of(c, i + 2), nlanes, A);
+        }
+        if (i + 1 < n) compute_chunk(c, rch, ren, chunk_of(c, i + 1), nlanes, B);
+        if (i + 2 < n) compute_chunk(c, rch, ren, chunk_of(c, i + 2), nlanes, A);
+    }
+};
+
+// TM: bit t set = the image holds units of granularity 2 << t somewhere (the residual set is always handled)
+template <int TM>
+__global__ __launch_bounds__(1024) void ecspmv_kernel(const ecs::EcsBatch batch)
 {
+    // which SpMV of the batch this workgroup works for (one item in the plain case)
+    uint32_t k = 0, block0 = 0;
+    while (k + 1 < batch.count && blockIdx.x >= batch.item[k].block_end) {
+        block0 = batch.item[k].block_end;
+        ++k;
+    }
+    const ecs::EcsBatchItem &it = batch.item[k];
+    const uint16_t *__restrict__ x = it.x;
+    uint16_t *__restrict__ y = it.y;
+    const uint32_t n = it.n, meta_stride = it.meta_stride, x_bytes = it.x_bytes;
+
     extern __shared__ uint4 lds4[];
     uint8_t *lds = reinterpret_cast<uint8_t *>(lds4);
     uint16_t *xs = reinterpret_cast<uint16_t *>(lds);
@@ -285,21 +336,8 @@ __global__ __launch_bounds__(1024) void ecspmv_kernel(const uint8_t *__restrict_
     float *slots = reinterpret_cast<float *>(lds + x_bytes + meta_stride);
 
     const uint32_t tid = threadIdx.x, nt = blockDim.x;
-    const uint8_t *panel = image + ECS_IMAGE_HEADER + (size_t)panel_stride * blockIdx.x;
+    const uint8_t *panel = it.image + ECS_IMAGE_HEADER + (size_t)it.panel_stride * (blockIdx.x - block0);
 
-    // stage the panel's tables and the whole of x in LDS (x is read from HBM once per XCD, then from L2)
-    for (uint32_t i = tid; i < meta_stride / 16; i += nt)
-        reinterpret_cast<uint4 *>(meta)[i] = reinterpret_cast<const uint4 *>(panel)[i];
-    if ((reinterpret_cast<uintptr_t>(x) & 15) == 0) {
-        const uint32_t nvec = n / 8;
-        for (uint32_t i = tid; i < nvec; i += nt) lds4[i] = reinterpret_cast<const uint4 *>(x)[i];
-        for (uint32_t i = nvec * 8 + tid; i < n; i += nt) xs[i] = x[i];
-    } else {
-        for (uint32_t i = tid; i < n; i += nt) xs[i] = x[i];
-    }
-    __syncthreads();
-
-    const uint32_t *hdr = reinterpret_cast<const uint32_t *>(meta);
     Ctx c;
     c.panel = panel;
     c.xs = xs;
@@ -309,11 +347,58 @@ __global__ __launch_bounds__(1024) void ecspmv_kernel(const uint8_t *__restrict_
     c.lane = tid & 63;
     c.nwaves = nt >> 6;
 
-    run_block_set<16>(c, hdr, 3);
-    run_block_set<8>(c, hdr, 2);
-    run_block_set<4>(c, hdr, 1);
-    run_block_set<2>(c, hdr, 0);
-    run_residual(c, hdr);
+    // Everything the workgroup needs first is requested at once, oldest first: the panel header (each wavefront
+    // reads it for itself: lane l holds word l), the panel's tables and x on their way to LDS.  All of these loads
+    // are unconditional (indices clamped), so none of them makes a later wait inexact.
+    const uint32_t hword = reinterpret_cast<const uint32_t *>(panel)[c.lane & 31u];
+    const uint4 *p4 = reinterpret_cast<const uint4 *>(panel);
+    const uint32_t nmeta = meta_stride / 16u;
+    const uint4 m0 = p4[min(tid, nmeta - 1u)], m1 = p4[min(tid + nt, nmeta - 1u)];
+    const uint32_t nvec = n / 8u;
+    const bool x_fast = (reinterpret_cast<uintptr_t>(x) & 15) == 0 && nvec > 0;
+    const uint4 *xsrc = x_fast ? reinterpret_cast<const uint4 *>(x) : p4;
+    const uint32_t xlast = x_fast ? nvec - 1u : 0u;
+    const uint4 x0 = xsrc[min(tid, xlast)], x1 = xsrc[min(tid + nt, xlast)];
+    const uint4 x2 = xsrc[min(tid + 2u * nt, xlast)], x3 = xsrc[min(tid + 3u * nt, xlast)];
+
+    // As soon as the header is here, the first two chunks of every set are requested, before anything is computed
+    // and before the tables and x have even reached LDS.
+    uint32_t hdr[ECS_PANEL_HEADER / 4];
+#pragma unroll
+    for (int w = 0; w < (int)(ECS_PANEL_HEADER / 4); ++w) hdr[w] = (uint32_t)__builtin_amdgcn_readlane((int)hword, w);
+    BlockSet<16> b16;
+    BlockSet<8> b8;
+    BlockSet<4> b4;
+    BlockSet<2> b2;
+    ResidualSet rs;
+    if constexpr ((TM & 8) != 0) b16.prologue(c, hdr, 3);
+    if constexpr ((TM & 4) != 0) b8.prologue(c, hdr, 2);
+    if constexpr ((TM & 2) != 0) b4.prologue(c, hdr, 1);
+    if constexpr ((TM & 1) != 0) b2.prologue(c, hdr, 0);
+    rs.prologue(c, hdr);
+
+    // tables and x into LDS
+    uint4 *meta4 = reinterpret_cast<uint4 *>(meta);
+    if (tid < nmeta) meta4[tid] = m0;
+    if (tid + nt < nmeta) meta4[tid + nt] = m1;
+    for (uint32_t i = tid + 2u * nt; i < nmeta; i += nt) meta4[i] = p4[i];
+    if (x_fast) {
+        if (tid < nvec) lds4[tid] = x0;
+        if (tid + nt < nvec) lds4[tid + nt] = x1;
+        if (tid + 2u * nt < nvec) lds4[tid + 2u * nt] = x2;
+        if (tid + 3u * nt < nvec) lds4[tid + 3u * nt] = x3;
+        for (uint32_t i = tid + 4u * nt; i < nvec; i += nt) lds4[i] = xsrc[i];
+        for (uint32_t i = nvec * 8u + tid; i < n; i += nt) xs[i] = x[i];
+    } else {
+        for (uint32_t i = tid; i < n; i += nt) xs[i] = x[i];
+    }
+    __syncthreads();
+
+    if constexpr ((TM & 8) != 0) b16.run(c);
+    if constexpr ((TM & 4) != 0) b8.run(c);
+    if constexpr ((TM & 2) != 0) b4.run(c);
+    if constexpr ((TM & 1) != 0) b2.run(c);
+    rs.run(c);
     __syncthreads();
 
     // every row: add its slots in a fixed order (16 lanes stride over them, then a fixed tree), store FP16
@@ -375,21 +460,32 @@ __global__ __launch_bounds__(1024) void stream_read_kernel(const uint4 *__restri
 
 namespace ecs {
 
-int launch_ecspmv(const void *d_image, const void *d_x, void *d_y, uint32_t n, uint32_t num_panels, uint32_t threads,
-                  uint32_t panel_stride, uint32_t meta_stride, uint32_t lds_bytes, void *stream)
+template <int TM>
+static int launch_tm(const EcsBatch &batch, uint32_t threads, uint32_t lds_bytes, void *stream)
 {
     static thread_local uint32_t attr_set_for = 0;
     if (lds_bytes > 65536 && lds_bytes > attr_set_for) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(ecspmv_kernel),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(ecspmv_kernel<TM>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
         if (e != hipSuccess) return (int)e;
         attr_set_for = lds_bytes;
     }
-    const uint32_t x_bytes = (n * 2u + 15u) / 16u * 16u;
-    hipLaunchKernelGGL(ecspmv_kernel, dim3(num_panels), dim3(threads), lds_bytes, (hipStream_t)stream,
-                       (const uint8_t *)d_image, (const uint16_t *)d_x, (uint16_t *)d_y, n, panel_stride, meta_stride,
-                       x_bytes);
+    const uint32_t grid = batch.item[batch.count - 1].block_end;
+    hipLaunchKernelGGL(ecspmv_kernel<TM>, dim3(grid), dim3(threads), lds_bytes, (hipStream_t)stream, batch);
     return (int)hipGetLastError();
+}
+
+int launch_ecspmv(const EcsBatch &batch, uint32_t threads, uint32_t lds_bytes, uint32_t type_mask, void *stream)
+{
+    // one instantiation per highest granularity present: sets that do not occur cost no registers
+    const int top = (type_mask & 8) ? 15 : (type_mask & 4) ? 7 : (type_mask & 2) ? 3 : (type_mask & 1) ? 1 : 0;
+    switch (top) {
+    case 15: return launch_tm<15>(batch, threads, lds_bytes, stream);
+    case 7: return launch_tm<7>(batch, threads, lds_bytes, stream);
+    case 3: return launch_tm<3>(batch, threads, lds_bytes, stream);
+    case 1: return launch_tm<1>(batch, threads, lds_bytes, stream);
+    default: return launch_tm<0>(batch, threads, lds_bytes, stream);
+    }
 }
 
 int launch_csr(const void *d_rowptr, const void *d_col, const void *d_val, const void *d_x, void *d_y, uint32_t m,

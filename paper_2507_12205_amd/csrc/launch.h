@@ -6,8 +6,23 @@
 
 namespace ecs {
 
-int launch_ecspmv(const void *d_image, const void *d_x, void *d_y, uint32_t n, uint32_t num_panels, uint32_t threads,
-                  uint32_t panel_stride, uint32_t meta_stride, uint32_t lds_bytes, void *stream);
+// One SpMV of a batched launch.  The table is passed to the kernel by value (kernel arguments).
+struct EcsBatchItem {
+    const uint8_t *image;     // device image of the matrix
+    const uint16_t *x;        // device, n FP16
+    uint16_t *y;              // device, m FP16
+    uint32_t n, panel_stride, meta_stride, x_bytes;
+    uint32_t block_end;       // workgroups [previous item's block_end, block_end) belong to this item
+    uint32_t pad_;
+};
+#define ECS_MAX_BATCH 16
+struct EcsBatch {
+    uint32_t count, pad_;
+    EcsBatchItem item[ECS_MAX_BATCH];
+};
+
+// Launches one kernel for all items (count <= ECS_MAX_BATCH, same workgroup size for all).
+int launch_ecspmv(const EcsBatch &batch, uint32_t threads, uint32_t lds_bytes, uint32_t type_mask, void *stream);
 int launch_csr(const void *d_rowptr, const void *d_col, const void *d_val, const void *d_x, void *d_y, uint32_t m,
                void *stream);
 int launch_stream_read(const void *d_buf, uint64_t bytes, void *d_out, uint32_t num_wg, void *stream);

@@ -222,3 +222,43 @@ def test_errors_from_the_abi(E):
     with pytest.raises(E.EcspmvError) as ei:
         A.ecspmv_upload(small.data_ptr(), 256, 0)
     assert ei.value.status == E.binding.ERR_TOO_SMALL
+
+
+def test_batched_launch_equals_single_launches(E):
+    """One launch over several independent SpMVs gives the same bits as one launch each."""
+    import torch
+    cfg = gen.scaled(gen.config(3), 4)
+    mats, xs, ys1, ys2 = [], [], [], []
+    for sid in (0, 4, 6, 0, 4):
+        W, x = gen.make_case(cfg, sid, copy=len(mats))
+        A = E.ecspmv_build_dense(W)
+        E.device.upload(A)
+        mats.append(A)
+        xs.append(torch.from_numpy(x.view(np.int16)).cuda().view(torch.float16))
+        ys1.append(torch.full((W.shape[0],), float("nan"), dtype=torch.float16, device="cuda"))
+        ys2.append(torch.full((W.shape[0],), float("nan"), dtype=torch.float16, device="cuda"))
+    sh = torch.cuda.current_stream().cuda_stream
+    for A, x, y in zip(mats, xs, ys1):
+        A.ecspmv_run(x.data_ptr(), y.data_ptr(), sh)
+    b = E.Batch(mats, [x.data_ptr() for x in xs], [y.data_ptr() for y in ys2])
+    b.ecspmv_run_batch(sh)
+    torch.cuda.synchronize()
+    for y1, y2 in zip(ys1, ys2):
+        a, c = y1.cpu().numpy(), y2.cpu().numpy()
+        assert not np.isnan(a.astype(np.float32)).any()
+        assert np.array_equal(a.view(np.uint16), c.view(np.uint16))
+
+
+def test_batch_larger_than_one_launch(E):
+    import torch
+    W, x = gen.small_random(64, 700, 0.4, 31)
+    A = E.ecspmv_build_dense(W)
+    E.device.upload(A)
+    xd = torch.from_numpy(x.view(np.int16)).cuda().view(torch.float16)
+    ys = [torch.full((64,), float("nan"), dtype=torch.float16, device="cuda") for _ in range(37)]
+    E.ecspmv_run_batch([A] * 37, [xd.data_ptr()] * 37, [y.data_ptr() for y in ys], torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    y_ref, S = orc.spmv_oracle(W, x)
+    for y in ys:
+        ok, ratio = orc.within_band(y.cpu().numpy(), y_ref, S, REL, ABS)
+        assert ok, ratio
