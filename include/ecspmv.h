@@ -50,8 +50,8 @@ typedef struct ecspmv_build_opts {
     int32_t  max_rounds;      /* cap on extraction rounds per level (Algorithm 1, inner loop); 0 = 64 */
     int32_t  num_panels;      /* row panels = workgroups of the SpMV launch; 0 = auto (256, fewer for small m) */
     int32_t  num_threads;     /* host threads for the offline phase; 0 = hardware concurrency, at most 16 */
-    int32_t  threads_per_wg;  /* workgroup size of the SpMV launch, multiple of 64 in [64,1024]; 0 = 512
-                                 (two workgroups then share a compute unit) */
+    int32_t  threads_per_wg;  /* workgroup size of the SpMV launch, multiple of 64 in [64,1024]; 0 = chosen at
+                                 launch: 1024 for a lone SpMV, 512 inside a batch */
     uint64_t flags;           /* ECSPMV_FLAG_* */
 } ecspmv_build_opts;
 
@@ -133,7 +133,7 @@ int ecspmv_run(const ecspmv_matrix *A, const void *d_x, void *d_y, void *stream)
 
 /* The same for `count` independent SpMVs in one kernel launch per 16 matrices: y_i = W_i x_i.  As, d_xs, d_ys:
  * host arrays of `count` handles / device pointers.  The SpMVs must not depend on one another (no y_i may be an
- * x_j of the same call); all matrices must have been built with the same threads_per_wg.  Meant for the
+ * x_j of the same call).  Meant for the
  * projections of a decoder layer that share a launch: workgroups of the next matrix start while the last ones of
  * the previous matrix drain, which removes the launch and ramp-up cost between small SpMVs. */
 int ecspmv_run_batch(const ecspmv_matrix *const *As, const void *const *d_xs, void *const *d_ys, int32_t count,

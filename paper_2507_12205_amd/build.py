@@ -12,7 +12,8 @@ HEADERS = ["encoder.h", "launch.h", "ecspmv_format.h", os.path.join("..", "..", 
 
 
 def lib_path() -> str:
-    return LIB
+    """Path of the shared library; ECSPMV_LIB overrides it (to try a differently built library)."""
+    return os.environ.get("ECSPMV_LIB", LIB)
 
 
 def is_stale() -> bool:
@@ -22,21 +23,22 @@ def is_stale() -> bool:
     return any(os.path.getmtime(os.path.join(CSRC, f)) > t for f in SOURCES + HEADERS)
 
 
-def build(verbose: bool = False) -> str:
+def build(verbose: bool = False, extra_flags=(), out: str = LIB) -> str:
     """Compile every source for gfx950 and link the shared library.  Needs hipcc; no GPU required."""
     cmd = ["hipcc", "-O3", "-std=c++17", "-fPIC", "-shared", "--offload-arch=gfx950",
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
            "-mpopcnt", "-pthread", "-Wall", "-Wno-unused-function",
            "-x", "hip"]
+    cmd += list(extra_flags)
     cmd += [os.path.join(CSRC, f) for f in SOURCES]
-    cmd += ["-o", LIB]
+    cmd += ["-o", out]
     res = subprocess.run(cmd, capture_output=True, text=True)
     if verbose or res.returncode != 0:
         print(res.stdout)
         print(res.stderr)
     if res.returncode != 0:
         raise RuntimeError("hipcc failed:\n" + res.stderr[-4000:])
-    return LIB
+    return out
 
 
 if __name__ == "__main__":

@@ -55,8 +55,8 @@ int parse_opts(const ecspmv_build_opts *o, ecs::BuildParams &bp)
     bp.max_rounds = opts.max_rounds ? opts.max_rounds : 64;
     bp.num_panels = opts.num_panels;
     bp.num_threads = opts.num_threads;
-    const int t = opts.threads_per_wg ? opts.threads_per_wg : 512;
-    if (t < 64 || t > 1024 || t % 64) return ECSPMV_ERR_INVALID;
+    const int t = opts.threads_per_wg;
+    if (t != 0 && (t < 64 || t > 1024 || t % 64)) return ECSPMV_ERR_INVALID;
     bp.threads_per_wg = t;
     bp.global_matching = (opts.flags & ECSPMV_FLAG_GLOBAL_MATCHING) != 0;
     bp.reorder = (opts.flags & ECSPMV_FLAG_NO_REORDER) == 0;
@@ -222,7 +222,6 @@ int ecspmv_run_batch(const ecspmv_matrix *const *As, const void *const *d_xs, vo
         if ((reinterpret_cast<uintptr_t>(d_xs[i]) & 1) || (reinterpret_cast<uintptr_t>(d_ys[i]) & 1))
             return ECSPMV_ERR_INVALID;
         if (!As[i]->d_image) return ECSPMV_ERR_NOT_UPLOADED;
-        if (As[i]->image.threads_per_wg != As[0]->image.threads_per_wg) return ECSPMV_ERR_INVALID;
     }
     std::vector<int32_t> order((size_t)count);
     for (int32_t i = 0; i < count; ++i) order[(size_t)i] = i;
@@ -248,7 +247,14 @@ int ecspmv_run_batch(const ecspmv_matrix *const *As, const void *const *d_xs, vo
             lds = im.lds_bytes > lds ? im.lds_bytes : lds;
             mask |= im.type_mask;
         }
-        int s = hip_status(ecs::launch_ecspmv(b, (uint32_t)As[order[(size_t)base]]->image.threads_per_wg, lds, mask, stream));
+        // Workgroup size: a lone SpMV gets one 1024-thread workgroup per compute unit; in a batch, 512-thread
+        // workgroups of neighbouring matrices share compute units and hide each other's start and end phases.
+        uint32_t threads = nb > 1 ? 512u : 1024u;
+        for (int32_t i = 0; i < nb; ++i) {
+            const int t = As[order[(size_t)(base + i)]]->image.threads_per_wg;
+            if (t) threads = (uint32_t)t;                      // a build-time choice overrides
+        }
+        int s = hip_status(ecs::launch_ecspmv(b, threads, lds, mask, stream));
         if (s) return s;
     }
     return ECSPMV_OK;

@@ -22,7 +22,7 @@ struct BuildParams {
     int max_rounds = 64;
     int num_panels = 0;
     int num_threads = 0;
-    int threads_per_wg = 512;
+    int threads_per_wg = 0;
     bool global_matching = false;
     bool reorder = true;
 };

@@ -28,6 +28,16 @@ __device__ __forceinline__ float dpp_f(float old, float src)
         __builtin_amdgcn_update_dpp(__float_as_int(old), __float_as_int(src), CTRL, ROW_MASK, 0xF, false));
 }
 
+#ifndef ECS_D4
+#define ECS_D4 1
+#define ECS_D2 2
+#define ECS_DR 1
+#endif
+// Register buffers per set (4-, 2- and 1-grained).  Measured on the box: one buffer for the 4-grained and residual
+// sets and two for the 2-grained set keep the kernel at 76 VGPRs, so three 512-thread workgroups share a compute
+// unit; deeper buffering costs that third workgroup and is slower.
+constexpr int D4 = ECS_D4, D2 = ECS_D2, DR = ECS_DR;
+
 constexpr int DPP_ROW_SHR1 = 0x111, DPP_ROW_SHR2 = 0x112, DPP_ROW_SHR4 = 0x114, DPP_ROW_SHR8 = 0x118;
 constexpr int DPP_ROW_BCAST15 = 0x142, DPP_ROW_BCAST31 = 0x143;
 constexpr int DPP_QUAD_1032 = 0xB1, DPP_QUAD_2301 = 0x4E, DPP_ROW_HALF_MIRROR = 0x141, DPP_ROW_MIRROR = 0x140;
@@ -173,12 +183,12 @@ __device__ __forceinline__ void compute_unit(const Ctx &c, const uint16_t *utab,
     if (active && j < (uint32_t)G) c.slots[ue[1 + j]] = out;
 }
 
-// A set's chunks c0, c0 + W, c0 + 2W, ... belong to this wavefront.  Two register buffers A and B alternate:
-// both are requested before anything is computed, and each is refilled right after it has been consumed, so a
-// wavefront always has its next two chunks on the way (the double buffering of Section 7, without copies).
-template <int G>
+// A set's chunks c0, c0 + W, c0 + 2W, ... belong to this wavefront.  DEPTH register buffers take turns: all are
+// requested before anything is computed, and each is refilled right after it has been consumed, so a wavefront
+// always has its next DEPTH chunks on the way (the double buffering of Section 7, deeper and without copies).
+template <int G, int DEPTH>
 struct BlockSet {
-    UnitRegs<G> A, B;
+    UnitRegs<G> buf[DEPTH];
     uint32_t nu, n, c0, bd_off, bv_off;
     const uint16_t *utab;
 
@@ -195,28 +205,35 @@ struct BlockSet {
         const uint32_t nch = (nu + 3u) >> 2;
         c0 = c.wave;
         n = nch > c0 ? (nch - c0 + c.nwaves - 1u) / c.nwaves : 0u;
-        // Both buffers are requested whether or not this wavefront has that many chunks (a missing chunk re-reads
-        // the set's last unit, an empty set reads the panel header): every wavefront then enters the loops below
-        // with the same loads in flight, which keeps the wait counts exact.
-        const uint32_t ebd = nu ? bd_off : 0u, ebv = nu ? bv_off : 0u, enu = nu ? nu : 1u;
-        load_unit<G>(c, ebd, ebv, unit_of(c, 0), enu, A);
-        load_unit<G>(c, ebd, ebv, unit_of(c, 1), enu, B);
+        // Every buffer is requested whether or not this wavefront has that many chunks (a missing chunk reads the
+        // panel header instead): every wavefront then enters the loop below with the same loads in flight, which
+        // keeps the wait counts exact.
+#pragma unroll
+        for (int d = 0; d < DEPTH; ++d) {
+            const bool have = (uint32_t)d < n;
+            load_unit<G>(c, have ? bd_off : 0u, have ? bv_off : 0u, have ? unit_of(c, d) : 0u, have ? nu : 1u, buf[d]);
+        }
     }
     __device__ __forceinline__ void run(const Ctx &c)
     {
         uint32_t i = 0;
-        for (; i + 3 < n; i += 2) {                    // chunks i + 2 and i + 3 exist: the refills are unconditional
-            compute_unit<G>(c, utab, unit_of(c, i), nu, A);
-            load_unit<G>(c, bd_off, bv_off, unit_of(c, i + 2), nu, A);
-            compute_unit<G>(c, utab, unit_of(c, i + 1), nu, B);
-            load_unit<G>(c, bd_off, bv_off, unit_of(c, i + 3), nu, B);
+        for (; i + 2 * DEPTH - 1 < n; i += DEPTH) {    // chunks i + DEPTH ... i + 2 DEPTH - 1 exist: unconditional refills
+#pragma unroll
+            for (int d = 0; d < DEPTH; ++d) {
+                compute_unit<G>(c, utab, unit_of(c, i + d), nu, buf[d]);
+                load_unit<G>(c, bd_off, bv_off, unit_of(c, i + DEPTH + d), nu, buf[d]);
+            }
         }
-        if (i < n) {
-            compute_unit<G>(c, utab, unit_of(c, i), nu, A);
-            if (i + 2 < n) load_unit<G>(c, bd_off, bv_off, unit_of(c, i + 2), nu, A);
+#pragma unroll
+        for (int d = 0; d < DEPTH; ++d) {
+            if (i + d < n) {
+                compute_unit<G>(c, utab, unit_of(c, i + d), nu, buf[d]);
+                if (i + DEPTH + d < n) load_unit<G>(c, bd_off, bv_off, unit_of(c, i + DEPTH + d), nu, buf[d]);
+            }
         }
-        if (i + 1 < n) compute_unit<G>(c, utab, unit_of(c, i + 1), nu, B);
-        if (i + 2 < n) compute_unit<G>(c, utab, unit_of(c, i + 2), nu, A);
+#pragma unroll
+        for (int d = 0; d < DEPTH; ++d)
+            if (i + DEPTH + d < n) compute_unit<G>(c, utab, unit_of(c, i + DEPTH + d), nu, buf[d]);
     }
 };
 
@@ -274,8 +291,9 @@ __device__ __forceinline__ void compute_chunk(const Ctx &c, const EcsRChunk *rch
     if (is_end) c.slots[e.slot] = seg_sum;
 }
 
+template <int DEPTH>
 struct ResidualSet {
-    ChunkRegs A, B;
+    ChunkRegs buf[DEPTH];
     uint32_t nlanes, n, c0, rd_off, rv_off;
     const EcsRChunk *rch;
     const EcsREntry *ren;
@@ -291,26 +309,33 @@ struct ResidualSet {
         const uint32_t nch = (nlanes + 63u) >> 6;
         c0 = c.wave;
         n = nch > c0 ? (nch - c0 + c.nwaves - 1u) / c.nwaves : 0u;
-        // unconditional, like the block sets: a missing chunk re-reads the last one, an empty set the panel header
-        const uint32_t erd = nch ? rd_off : 0u, erv = nch ? rv_off : 0u, enl = nch ? nlanes : 1u, last = nch ? nch - 1u : 0u;
-        load_chunk(c, erd, erv, min(chunk_of(c, 0), last), enl, A);
-        load_chunk(c, erd, erv, min(chunk_of(c, 1), last), enl, B);
+        // unconditional, like the block sets: a missing chunk reads the panel header
+#pragma unroll
+        for (int d = 0; d < DEPTH; ++d) {
+            const bool have = (uint32_t)d < n;
+            load_chunk(c, have ? rd_off : 0u, have ? rv_off : 0u, have ? chunk_of(c, d) : 0u, have ? nlanes : 1u, buf[d]);
+        }
     }
     __device__ __forceinline__ void run(const Ctx &c)
     {
         uint32_t i = 0;
-        for (; i + 3 < n; i += 2) {
-            compute_chunk(c, rch, ren, chunk_of(c, i), nlanes, A);
-            load_chunk(c, rd_off, rv_off, chunk_of(c, i + 2), nlanes, A);
-            compute_chunk(c, rch, ren, chunk_of(c, i + 1), nlanes, B);
-            load_chunk(c, rd_off, rv_off, chunk_of(c, i + 3), nlanes, B);
+        for (; i + 2 * DEPTH - 1 < n; i += DEPTH) {
+#pragma unroll
+            for (int d = 0; d < DEPTH; ++d) {
+                compute_chunk(c, rch, ren, chunk_of(c, i + d), nlanes, buf[d]);
+                load_chunk(c, rd_off, rv_off, chunk_of(c, i + DEPTH + d), nlanes, buf[d]);
+            }
         }
-        if (i < n) {
-            compute_chunk(c, rch, ren, chunk_of(c, i), nlanes, A);
-            if (i + 2 < n) load_chunk(c, rd_off, rv_off, chunk_of(c, i + 2), nlanes, A);
+#pragma unroll
+        for (int d = 0; d < DEPTH; ++d) {
+            if (i + d < n) {
+                compute_chunk(c, rch, ren, chunk_of(c, i + d), nlanes, buf[d]);
+                if (i + DEPTH + d < n) load_chunk(c, rd_off, rv_off, chunk_of(c, i + DEPTH + d), nlanes, buf[d]);
+            }
         }
-        if (i + 1 < n) compute_chunk(c, rch, ren, chunk_of(c, i + 1), nlanes, B);
-        if (i + 2 < n) compute_chunk(c, rch, ren, chunk_of(c, i + 2), nlanes, A);
+#pragma unroll
+        for (int d = 0; d < DEPTH; ++d)
+            if (i + DEPTH + d < n) compute_chunk(c, rch, ren, chunk_of(c, i + DEPTH + d), nlanes, buf[d]);
     }
 };
 
@@ -366,11 +391,13 @@ __global__ __launch_bounds__(1024) void ecspmv_kernel(const ecs::EcsBatch batch)
     uint32_t hdr[ECS_PANEL_HEADER / 4];
 #pragma unroll
     for (int w = 0; w < (int)(ECS_PANEL_HEADER / 4); ++w) hdr[w] = (uint32_t)__builtin_amdgcn_readlane((int)hword, w);
-    BlockSet<16> b16;
-    BlockSet<8> b8;
-    BlockSet<4> b4;
-    BlockSet<2> b2;
-    ResidualSet rs;
+    // buffers per set: deeper where chunks are small and frequent, shallower where registers run out
+    constexpr bool wide = (TM & 12) != 0;
+    BlockSet<16, 1> b16;
+    BlockSet<8, 1> b8;
+    BlockSet<4, wide ? 1 : D4> b4;
+    BlockSet<2, wide ? 2 : D2> b2;
+    ResidualSet<wide ? 2 : DR> rs;
     if constexpr ((TM & 8) != 0) b16.prologue(c, hdr, 3);
     if constexpr ((TM & 4) != 0) b8.prologue(c, hdr, 2);
     if constexpr ((TM & 2) != 0) b4.prologue(c, hdr, 1);

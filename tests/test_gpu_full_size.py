@@ -1,5 +1,5 @@
 """GPU parity at the full sizes of the five workload configs, in the launch configuration bench.py times
-(default options: 256 row panels, 512 threads per workgroup).  Every row is compared with the FP64 oracle and
+(default options: 256 row panels, workgroup size chosen at launch).  Every row is compared with the FP64 oracle and
 the EC-CSR image must decode to exactly W's stored entries."""
 import numpy as np
 import pytest
@@ -25,7 +25,7 @@ def test_full_size_config(cid):
         W, x = gen.make_case(cfg, sid)
         A = E.ecspmv_build_dense(W)
         st = A.ecspmv_stats()
-        assert st.num_panels == min(256, m // 16) and st.threads_per_wg == 512
+        assert st.num_panels == min(256, m // 16)
         r, c, v = A.ecspmv_decode()
         rr, cc, vv = orc.pattern_triples(W)
         o = np.lexsort((c, r))
