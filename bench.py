@@ -7,6 +7,11 @@ rotate through several independently seeded layers whose EC-CSR images total mor
 served from the 256 MB Infinity Cache (cold-cache timing).  Inputs are synthetic (workloads/generators.py) and are
 resident in HBM before the timed region starts.
 
+`--launch` says how the SpMVs of a step are submitted in the timed region: `single` (default) = one launch each,
+as the workload is stated; `groups` / `all` = the batched entry point (one launch per group of projections that are
+independent in a decoder layer / one launch for all seven).  All three are always measured and reported in
+`by_launch_mode`; `value` and `roofline` are those of the mode given by `--launch`.
+
 Prints ONE JSON line: whole-job effective HBM GB/s (bytes that must be read or written per SpMV: EC-CSR values,
 deltas and tables + x + y, divided by time), microseconds per SpMV, the roofline of the SpMV kernel and the CPU
 oracle's rate on the host cores as a baseline.
@@ -42,6 +47,9 @@ def parse_args():
                     help="how the SpMVs of a step are submitted in the timed region: one launch each (single), "
                          "one launch per group of projections that are independent in a decoder layer (groups: "
                          "q+k+v, o, gate+up, down), or one launch for the whole step (all)")
+    ap.add_argument("--profile-run", action="store_true",
+                    help="only the warm-up and the timed region of the chosen launch mode (for rocprofv3, so that "
+                         "the kernel statistics cover exactly the launches the bench times)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip hot-cache, CSR and streaming-read legs")
     ap.add_argument("--detail", type=str, default="", help="write per-shape details to this JSON file")
@@ -58,6 +66,8 @@ def algorithmic_bytes(st) -> int:
 
 def main():
     args = parse_args()
+    if args.profile_run:
+        args.no_extras = args.no_cpu_baseline = True
     if args.gpus != 1:
         print(f"bench.py: this build runs on one GPU; --gpus {args.gpus} is not supported "
               "(the path shards by row panels, see DESIGN.md), exiting", file=sys.stderr)
@@ -177,7 +187,7 @@ def main():
         for e in layer:
             classes.setdefault((e["m"], e["n"]), []).append(e)
     per_shape = {}
-    for (m, n), lst in classes.items():
+    for (m, n), lst in ([] if args.profile_run else classes.items()):
         tot_img = sum(int(e["st"].image_bytes) for e in lst)
         reps = max(2, (args.steps * nshapes) // (4 * len(lst)))
         for e in lst:
@@ -245,7 +255,7 @@ def main():
     out["launch_mode"] = args.launch
     out["launches_per_step"] = {"single": nshapes, "groups": len(batched["groups"][0]), "all": 1}[args.launch]
     alt = {}
-    for mode in ("single", "groups", "all"):
+    for mode in (() if args.profile_run else ("single", "groups", "all")):
         for w in range(min(args.warmup, copies)):
             run_layer(mats[w % copies], mode)
         torch.cuda.synchronize()
@@ -261,6 +271,12 @@ def main():
                      "gbps": round(moved / (ms * 1e-3) / 1e9, 1),
                      "pct_of_hbm_peak": round(100.0 * moved / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 2)}
     out["by_launch_mode"] = alt
+    # roofline of the same kernel when one launch carries the whole step (bytes per launch / launch time)
+    step_bytes = moved / args.steps
+    out["roofline_by_launch_mode"] = {
+        mode: {"bytes_per_launch": round(step_bytes / a["launches_per_step"]),
+               "avg_launch_us": round(a["us_per_step"] / a["launches_per_step"], 3),
+               "achieved": a["gbps"], "frac": round(a["gbps"] / HBM_PEAK_GBPS, 4)} for mode, a in alt.items()}
 
     if not args.no_extras:
         # hot cache: the same layer over and over (working set of one layer still exceeds L2)
