@@ -1,0 +1,168 @@
+"""Pins for the extraction oracle (hand-derived block sets) and parity of the library's encoder with it.
+
+A "group" below is 16 consecutive columns, so that 4 groups make one 64-column unit: the paper's small examples
+(Section 4.3: a row that shares four columns with one row and four others with another) carry over with one paper
+column = one group."""
+import numpy as np
+import pytest
+
+import paper_2507_12205_amd as E
+from paper_2507_12205_amd import binding as B
+from oracle import extraction_oracle as xo
+from workloads import generators as gen
+
+
+def groups(*ids):
+    return {16 * g + k for g in ids for k in range(16)}
+
+
+def as_sets(block_sets):
+    return {g: sorted((tuple(r), tuple(c)) for r, c in units) for g, units in block_sets.items()}
+
+
+# ---- pins: expected results derived by hand from Algorithms 1 and 2 ----------------------------------------
+
+def test_pin_row_split_between_two_partners():
+    """Rows 0 and 1 are disjoint; row 2 holds both their column sets.  Round 1: row 2 is popped first (most
+    columns), both partners share 64 columns, the tie goes to row 0 -> block (2, 0) over row 0's columns.
+    Round 2: rows 1 and 2 now hold 64 columns each; the tie in the pop order goes to row 1, which takes row 2 ->
+    block (1, 2).  Nothing remains, no level-2 block (the two blocks share row 2 but no column)."""
+    rows = [groups(3, 4, 5, 6), groups(0, 2, 7, 8), groups(0, 2, 3, 4, 5, 6, 7, 8)]
+    bs, resid = xo.hierarchical_block_extraction(rows)
+    assert as_sets(bs) == {2: sorted([((2, 0), tuple(sorted(groups(3, 4, 5, 6)))),
+                                      ((1, 2), tuple(sorted(groups(0, 2, 7, 8))))])}
+    assert resid == [[], [], []]
+
+
+def test_pin_identical_rows_climb_every_level():
+    """Four identical rows of 128 columns: level 0 pairs (0,1) and (2,3); level 1 pairs the two blocks; the
+    result is two 4-grained units with member order (0,1,2,3) and nothing else."""
+    cols = groups(*range(8))
+    bs, resid = xo.hierarchical_block_extraction([set(cols) for _ in range(4)], max_granularity=8)
+    s = sorted(cols)
+    assert as_sets(bs) == {4: [((0, 1, 2, 3), tuple(s[:64])), ((0, 1, 2, 3), tuple(s[64:]))]}
+    assert resid == [[], [], [], []]
+    bs2, _ = xo.hierarchical_block_extraction([set(cols) for _ in range(4)], max_granularity=2)
+    assert as_sets(bs2) == {2: [((0, 1), tuple(s[:64])), ((0, 1), tuple(s[64:])),
+                                ((2, 3), tuple(s[:64])), ((2, 3), tuple(s[64:]))]}
+
+
+def test_pin_leftover_below_a_unit_stays_residual():
+    rows = [set(range(100)), set(range(100))]
+    bs, resid = xo.hierarchical_block_extraction(rows)
+    assert as_sets(bs) == {2: [((0, 1), tuple(range(64)))]}
+    assert resid == [list(range(64, 100))] * 2
+
+
+def test_pin_gap_wider_than_delta_range_breaks_a_unit():
+    cols = set(range(40)) | set(range(1000, 1040))          # two runs of 40 columns, 961 apart
+    bs, resid = xo.hierarchical_block_extraction([set(cols), set(cols)])
+    assert bs == {} and resid == [sorted(cols)] * 2
+    cols = set(range(40)) | set(range(294, 334))            # gap of exactly 255: still one unit
+    bs, resid = xo.hierarchical_block_extraction([set(cols), set(cols)])
+    s = sorted(cols)
+    assert as_sets(bs) == {2: [((0, 1), tuple(s[:64]))]} and resid == [s[64:]] * 2
+
+
+def test_pin_partner_choice_and_pop_order():
+    """Row 3 has the most columns and is popped first; it shares 128 columns with row 1 and 64 with rows 0 and 2,
+    so it takes row 1.  Rows 0 and 2 (64 identical columns) are left for each other."""
+    rows = [groups(0, 1, 2, 3), groups(4, 5, 6, 7, 8, 9, 10, 11), groups(0, 1, 2, 3),
+            groups(0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12)]
+    bs, resid = xo.hierarchical_block_extraction(rows, max_granularity=2)
+    s1 = sorted(groups(4, 5, 6, 7, 8, 9, 10, 11))
+    assert as_sets(bs) == {2: sorted([((3, 1), tuple(s1[:64])), ((3, 1), tuple(s1[64:])),
+                                      ((0, 2), tuple(sorted(groups(0, 1, 2, 3))))])}
+    assert resid[3] == sorted(groups(0, 1, 2, 3, 12)) and resid[0] == resid[1] == resid[2] == []
+
+
+def test_pin_form_units_rule():
+    taken, rest = xo.form_units(list(range(0, 130, 2)) + [1000], 64, 255)
+    assert taken == list(range(0, 128, 2)) and rest == [128, 1000]
+    taken, rest = xo.form_units([0, 300] + list(range(301, 364)), 64, 255)      # the gap drops column 0 only
+    assert taken == [300] + list(range(301, 364)) and rest == [0]
+
+
+def test_partition_invariant_on_random_rows():
+    rng = np.random.default_rng(1)
+    p = rng.uniform(0.1, 0.9, 3000)
+    rows = [set(np.nonzero(rng.random(3000) < p)[0].tolist()) for _ in range(12)]
+    bs, resid = xo.hierarchical_block_extraction(rows, max_granularity=8)
+    seen = [set(r) for r in resid]
+    for g, units in bs.items():
+        for members, cols in units:
+            assert len(members) == g == len(set(members)) and len(cols) == 64
+            assert all(b - a <= 255 and b > a for a, b in zip(cols, cols[1:]))
+            for m in members:
+                assert not (seen[m] & set(cols))                 # no entry twice
+                seen[m] |= set(cols)
+    assert seen == rows                                          # every entry exactly once
+    assert bs.get(2) and bs.get(4)
+
+
+def test_panel_bounds_rule():
+    assert xo.nnz_balanced_panels([1] * 8, 4) == [0, 2, 4, 6, 8]
+    assert xo.nnz_balanced_panels([10, 0, 0, 0, 10, 0, 0, 0], 2) == [0, 4, 8]
+    assert xo.nnz_balanced_panels([0] * 6, 4) == [0, 2, 4, 5, 6]
+    assert xo.nnz_balanced_panels([5, 5, 5], 8) == [0, 1, 2, 3]
+
+
+# ---- parity: the library's encoder against the oracle -------------------------------------------------------
+
+def library_block_sets(A):
+    g, rows, cols = A.ecspmv_block_sets()
+    out, p = {}, 0
+    for u in range(len(g)):
+        out.setdefault(int(g[u]), []).append((tuple(int(v) for v in rows[p:p + g[u]]), tuple(int(v) for v in cols[u])))
+        p += g[u]
+    return {k: sorted(v) for k, v in out.items()}
+
+
+def oracle_for_matrix(W, bounds, max_g):
+    pat = (W.view(np.uint16) & 0x7FFF) != 0
+    blocks, resid = {}, {}
+    for r0, r1 in zip(bounds[:-1], bounds[1:]):
+        rows = [set(np.nonzero(pat[i])[0].tolist()) for i in range(r0, r1)]
+        bs, rs = xo.hierarchical_block_extraction(rows, max_granularity=max_g)
+        for g, units in bs.items():
+            blocks.setdefault(g, []).extend((tuple(r0 + m for m in mem), cols) for mem, cols in units)
+        for i, c in enumerate(rs):
+            resid[r0 + i] = c
+    return {k: sorted(v) for k, v in blocks.items()}, resid
+
+
+def library_residual(A, m):
+    import pyformat
+    resid = {i: [] for i in range(m)}
+    for u in pyformat.walk(A.ecspmv_export_image()):
+        if u["kind"] == "lane":
+            keep = (u["values"] & 0x7FFF) != 0
+            resid[u["row"]].extend(int(c) for c in u["cols"][keep])
+    return resid
+
+
+@pytest.mark.parametrize("maxg", [2, 4, 8, 16])
+def test_encoder_matches_oracle_matching_over_all_rows(maxg):
+    """One panel = the whole matrix: row matching over all rows, as the algorithm is printed."""
+    cfg = gen.scaled(gen.config(3), 4)
+    W = gen.make_matrix(cfg, 0)[:96]
+    A = E.ecspmv_build_dense(W, E.make_opts(max_granularity=maxg, flags=B.FLAG_GLOBAL_MATCHING))
+    want, want_res = oracle_for_matrix(W, [0, W.shape[0]], maxg)
+    assert library_block_sets(A) == want
+    assert library_residual(A, W.shape[0]) == want_res
+    assert sum(len(v) for v in want.values()) > 50
+
+
+@pytest.mark.parametrize("cid,div,panels", [(1, 16, 0), (3, 8, 0), (4, 8, 40), (0, 1, 0)])
+def test_encoder_matches_oracle_per_panel(cid, div, panels):
+    cfg = gen.scaled(gen.config(cid), div) if div > 1 else gen.config(cid)
+    W = gen.make_matrix(cfg, 0)
+    m = W.shape[0]
+    A = E.ecspmv_build_dense(W, E.make_opts(num_panels=panels))
+    P = A.ecspmv_stats().num_panels
+    assert P == (panels or min(256, max(1, m // 16)))
+    nnz = np.count_nonzero(W.view(np.uint16) & 0x7FFF, axis=1).tolist()
+    bounds = xo.nnz_balanced_panels(nnz, P)
+    want, want_res = oracle_for_matrix(W, bounds, 8)
+    assert library_block_sets(A) == want
+    assert library_residual(A, m) == want_res
