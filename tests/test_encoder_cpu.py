@@ -57,6 +57,13 @@ def test_error_paths_without_gpu():
     assert lib.ecspmv_decode(A._h, ctypes.byref(n), buf.ctypes.data, buf.ctypes.data, v.ctypes.data) == B.ERR_TOO_SMALL
     assert lib.ecspmv_run(A._h, ctypes.c_void_p(16), ctypes.c_void_p(32), None) == B.ERR_NOT_UPLOADED
     assert lib.ecspmv_run(None, None, None, None) == B.ERR_INVALID
+    hs = (ctypes.c_void_p * 2)(A._h.value, A._h.value)
+    ptrs = (ctypes.c_void_p * 2)(16, 32)
+    assert lib.ecspmv_run_batch(hs, ptrs, ptrs, 2, None) == B.ERR_NOT_UPLOADED
+    assert lib.ecspmv_run_batch(hs, ptrs, ptrs, 0, None) == B.ERR_INVALID
+    assert lib.ecspmv_run_batch(None, ptrs, ptrs, 2, None) == B.ERR_INVALID
+    odd = (ctypes.c_void_p * 2)(17, 32)
+    assert lib.ecspmv_run_batch(hs, odd, ptrs, 2, None) == B.ERR_INVALID
     lib.ecspmv_destroy(None)                                                                                 # no-op
     assert lib.ecspmv_strerror(B.ERR_TOO_SMALL).decode() == "buffer too small"
 

@@ -262,3 +262,24 @@ def test_batch_larger_than_one_launch(E):
     for y in ys:
         ok, ratio = orc.within_band(y.cpu().numpy(), y_ref, S, REL, ABS)
         assert ok, ratio
+
+
+@pytest.mark.parametrize("n", [40000, 65535])
+def test_widest_supported_x(E, n):
+    """x of up to 65535 entries (128 KB) still fits LDS next to the tables; needs the large-LDS launch attribute."""
+    rng = np.random.default_rng(n)
+    m = 48
+    W = np.zeros((m, n), dtype=np.float16)
+    mask = rng.random((m, n)) < 0.05
+    W[mask] = (rng.standard_normal(int(mask.sum())) * 0.02).astype(np.float16)
+    W[:, n - 1] = 0.5                                  # the last column is used by every row
+    x = gen.make_vector(n, seed=n)
+    A, y = check(E, W, x, label=f"wide_x_{n}")
+    assert A.ecspmv_stats().lds_bytes > 2 * n
+
+
+def test_too_wide_is_refused_on_the_host(E):
+    W = np.zeros((2, 65536), dtype=np.float16)
+    with pytest.raises(E.EcspmvError) as ei:
+        E.ecspmv_build_dense(W)
+    assert ei.value.status == E.binding.ERR_UNSUPPORTED
