@@ -1,0 +1,69 @@
+"""Randomised checks over many small shapes and option sets (seeded): round trip on the CPU, parity on the GPU."""
+import numpy as np
+import pytest
+
+import paper_2507_12205_amd as E
+from paper_2507_12205_amd import binding as B
+from oracle import oracle as orc
+
+
+def random_case(rng):
+    m = int(rng.integers(1, 140))
+    n = int(rng.choice([1, 7, 63, 64, 65, 200, 513, 1024, 3000]))
+    style = rng.integers(0, 4)
+    if style == 0:                                   # i.i.d.
+        mask = rng.random((m, n)) < rng.uniform(0.01, 0.9)
+    elif style == 1:                                 # column-correlated: many shared columns
+        p = rng.beta(0.5, 0.5, n)
+        mask = rng.random((m, n)) < p[None, :]
+    elif style == 2:                                 # few distinct row patterns, repeated
+        k = int(rng.integers(1, 5))
+        pats = rng.random((k, n)) < rng.uniform(0.2, 0.8)
+        mask = pats[rng.integers(0, k, m)]
+    else:                                            # banded / clustered with wide gaps
+        mask = np.zeros((m, n), dtype=bool)
+        for i in range(m):
+            for _ in range(int(rng.integers(0, 4))):
+                a = int(rng.integers(0, n))
+                mask[i, a:a + int(rng.integers(1, 90))] = True
+    W = np.where(mask, rng.standard_normal((m, n)) * 0.02, 0.0).astype(np.float16)
+    x = rng.standard_normal(n).astype(np.float16)
+    opts = dict(max_granularity=int(rng.choice([0, 1, 2, 4, 8, 16])),
+                num_panels=int(rng.choice([0, 1, 2, 5, 300])),
+                flags=int(rng.choice([0, 0, B.FLAG_NO_REORDER, B.FLAG_GLOBAL_MATCHING])))
+    return W, x, opts
+
+
+def test_roundtrip_random_cpu():
+    rng = np.random.default_rng(2024)
+    for it in range(120):
+        W, _, opts = random_case(rng)
+        A = E.ecspmv_build_dense(W, E.make_opts(**opts))
+        r, c, v = A.ecspmv_decode()
+        rr, cc, vv = orc.pattern_triples(W)
+        o = np.lexsort((c, r))
+        assert np.array_equal(r[o], rr) and np.array_equal(c[o], cc) and np.array_equal(v[o], vv), (it, W.shape, opts)
+        st = A.ecspmv_stats()
+        assert sum(st.nnz_by_g) == st.nnz == len(rr)
+
+
+@pytest.mark.gpu
+def test_parity_random_gpu():
+    import torch
+    from paper_2507_12205_amd import device as D
+    rng = np.random.default_rng(77)
+    for it in range(80):
+        W, x, opts = random_case(rng)
+        opts["threads_per_wg"] = int(rng.choice([0, 64, 256, 512, 1024]))
+        print(f"[case] {it} shape={W.shape} opts={opts}", flush=True)
+        A = E.ecspmv_build_dense(W, E.make_opts(**opts))
+        D.upload(A)
+        xd = torch.from_numpy(x.view(np.int16)).cuda().view(torch.float16)
+        yd = torch.full((W.shape[0],), float("nan"), dtype=torch.float16, device="cuda")
+        D.run(A, xd, yd)
+        torch.cuda.synchronize()
+        y = yd.cpu().numpy()
+        y_ref, S = orc.spmv_oracle(W, x)
+        assert not np.isnan(y.astype(np.float32)).any()
+        ok, ratio = orc.within_band(y, y_ref, S, 2e-3, 1e-6)
+        assert ok, (it, W.shape, opts, ratio)
