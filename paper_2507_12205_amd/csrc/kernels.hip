@@ -140,10 +140,12 @@ __device__ __forceinline__ void load_unit(const Ctx &c, uint32_t bd_off, uint32_
 {
     const uint32_t j = c.lane & 15;
     const uint32_t uu = min(u, nu - 1u);
-    r.d = load4(c.panel + bd_off + 64u * uu + 4u * j);
-    const uint8_t *pv = c.panel + bv_off + (128u * G) * uu + 16u * j;
+    // one 32-bit offset from the (wave-uniform) panel pointer per load: scalar base + vector offset addressing
+    const uint32_t od = bd_off + 64u * uu + 4u * j;
+    const uint32_t ov = bv_off + (128u * G) * uu + 16u * j;
+    r.d = load4(c.panel + od);
 #pragma unroll
-    for (int k = 0; k < G / 2; ++k) r.v[k] = load16(pv + 256u * k);
+    for (int k = 0; k < G / 2; ++k) r.v[k] = load16(c.panel + (ov + 256u * k));
 }
 
 template <int G>
@@ -248,10 +250,11 @@ __device__ __forceinline__ void load_chunk(const Ctx &c, uint32_t rd_off, uint32
 {
     const uint32_t nl = min(64u, nlanes - 64u * ch);
     const uint32_t ll = min(c.lane, nl - 1u);           // lanes beyond the chunk's end re-read its last lane unit
-    r.d = load16(c.panel + rd_off + 1024u * ch + 16u * ll);
-    const uint8_t *pv = c.panel + rv_off + 2048u * ch + 16u * ll;
-    r.v0 = load16(pv);
-    r.v1 = load16(pv + 16u * nl);
+    const uint32_t od = rd_off + 1024u * ch + 16u * ll;
+    const uint32_t ov = rv_off + 2048u * ch + 16u * ll;
+    r.d = load16(c.panel + od);
+    r.v0 = load16(c.panel + ov);
+    r.v1 = load16(c.panel + (ov + 16u * nl));
 }
 
 __device__ __forceinline__ void compute_chunk(const Ctx &c, const EcsRChunk *rch, const EcsREntry *ren, uint32_t ch,
