@@ -32,7 +32,7 @@ extern "C" {
 
 #define ECSPMV_OK                 0
 #define ECSPMV_ERR_INVALID       -1  /* NULL pointer, bad size, ld < n, unsorted / duplicate / out-of-range CSR column */
-#define ECSPMV_ERR_UNSUPPORTED   -2  /* n > 65535, delta_bits != 8, max_granularity not in {1,2,4,8,16}, too many rows */
+#define ECSPMV_ERR_UNSUPPORTED   -2  /* n > 65535, delta_bits not 4 or 8, max_granularity not in {1,2,4,8,16}, too many rows */
 #define ECSPMV_ERR_NOMEM         -3  /* host allocation failed */
 #define ECSPMV_ERR_HIP           -4  /* a HIP call failed; ecspmv_last_hip_error() has its code */
 #define ECSPMV_ERR_NOT_UPLOADED  -5  /* ecspmv_run before ecspmv_upload */
@@ -45,7 +45,9 @@ typedef struct ecspmv_csr ecspmv_csr;           /* opaque: plain CSR (comparison
  * defaults.  Fields beyond struct_size are taken as 0 (= default). */
 typedef struct ecspmv_build_opts {
     uint32_t struct_size;     /* sizeof(ecspmv_build_opts) as the caller compiled it */
-    int32_t  delta_bits;      /* width of a delta index (Section 6.2, range R_P = 2^bits); 0 = 8; only 8 is built */
+    int32_t  delta_bits;      /* width of a delta index (Section 6.2, range R_P = 2^bits): 8 (EC-CSR-8) or 4
+                                 (EC-CSR-4, Section 8.2: zero fillers every 15 columns, blocks only where 64 shared
+                                 columns follow one another within 15); 0 = 8 */
     int32_t  max_granularity; /* largest block granularity g (rows per block, Section 4); 0 = 8; 1 = no extraction */
     int32_t  max_rounds;      /* cap on extraction rounds per level (Algorithm 1, inner loop); 0 = 64 */
     int32_t  num_panels;      /* row panels = workgroups of the SpMV launch; 0 = auto (256, fewer for small m) */
@@ -80,6 +82,7 @@ typedef struct ecspmv_stats_t {
     double   x_access_cost;            /* sum over stored entries of 1/g(e): the paper's x-access objective with L = 1 */
     double   build_seconds;
     int64_t  delta_hist[9];            /* residual deltas: 0, 1, 2-3, 4-7, ..., 64-127, 128-255 */
+    int32_t  delta_bits, reserved_;    /* delta width the image was built with */
 } ecspmv_stats_t;
 
 /* ---- offline phase (host) -------------------------------------------------------------------------- */
@@ -131,7 +134,8 @@ int ecspmv_upload(ecspmv_matrix *A, void *d_buf, size_t bytes, void *stream);
  * x must be finite: padding zeros are multiplied with x entries. */
 int ecspmv_run(const ecspmv_matrix *A, const void *d_x, void *d_y, void *stream);
 
-/* The same for `count` independent SpMVs in one kernel launch per 16 matrices: y_i = W_i x_i.  As, d_xs, d_ys:
+/* The same for `count` independent SpMVs in one kernel launch per 16 matrices (a launch also ends where the
+ * delta width changes from one matrix to the next): y_i = W_i x_i.  As, d_xs, d_ys:
  * host arrays of `count` handles / device pointers.  The SpMVs must not depend on one another (no y_i may be an
  * x_j of the same call).  Meant for the
  * projections of a decoder layer that share a launch: workgroups of the next matrix start while the last ones of

@@ -41,7 +41,8 @@ class Stats(Structure):
                 ("pad_elements", c_int64), ("gap_pad_elements", c_int64), ("num_panels", c_int32),
                 ("threads_per_wg", c_int32), ("panel_stride", c_int64), ("meta_stride", c_int64),
                 ("lds_bytes", c_int64), ("max_panel_bytes", c_int64), ("min_panel_bytes", c_int64),
-                ("x_access_cost", c_double), ("build_seconds", c_double), ("delta_hist", c_int64 * 9)]
+                ("x_access_cost", c_double), ("build_seconds", c_double), ("delta_hist", c_int64 * 9),
+                ("delta_bits", c_int32), ("reserved_", c_int32)]
 
     def as_dict(self) -> dict:
         out = {}

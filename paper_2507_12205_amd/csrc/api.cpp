@@ -47,7 +47,8 @@ int parse_opts(const ecspmv_build_opts *o, ecs::BuildParams &bp)
         if (o->struct_size < sizeof(uint32_t)) return ECSPMV_ERR_INVALID;
         std::memcpy(&opts, o, o->struct_size < sizeof(opts) ? o->struct_size : sizeof(opts));
     }
-    if (opts.delta_bits != 0 && opts.delta_bits != 8) return ECSPMV_ERR_UNSUPPORTED;
+    if (opts.delta_bits != 0 && opts.delta_bits != 8 && opts.delta_bits != 4) return ECSPMV_ERR_UNSUPPORTED;
+    bp.delta_bits = opts.delta_bits ? opts.delta_bits : 8;
     const int g = opts.max_granularity ? opts.max_granularity : 8;
     if (g != 1 && g != 2 && g != 4 && g != 8 && g != 16) return ECSPMV_ERR_UNSUPPORTED;
     bp.max_granularity = g;
@@ -225,8 +226,11 @@ int ecspmv_run_batch(const ecspmv_matrix *const *As, const void *const *d_xs, vo
     }
     std::vector<int32_t> order((size_t)count);
     for (int32_t i = 0; i < count; ++i) order[(size_t)i] = i;
-    for (int32_t base = 0; base < count; base += ECS_MAX_BATCH) {       // one launch per ECS_MAX_BATCH matrices
-        const int32_t nb = count - base < ECS_MAX_BATCH ? count - base : ECS_MAX_BATCH;
+    // one launch per run of up to ECS_MAX_BATCH matrices with the same delta width
+    for (int32_t base = 0, nb = 0; base < count; base += nb) {
+        const int bits = As[order[(size_t)base]]->image.delta_bits;
+        for (nb = 1; base + nb < count && nb < ECS_MAX_BATCH; ++nb)
+            if (As[order[(size_t)(base + nb)]]->image.delta_bits != bits) break;
         ecs::EcsBatch b;
         std::memset(&b, 0, sizeof(b));
         b.count = (uint32_t)nb;
@@ -254,7 +258,7 @@ int ecspmv_run_batch(const ecspmv_matrix *const *As, const void *const *d_xs, vo
             const int t = As[order[(size_t)(base + i)]]->image.threads_per_wg;
             if (t) threads = (uint32_t)t;                      // a build-time choice overrides
         }
-        int s = hip_status(ecs::launch_ecspmv(b, threads, lds, mask, stream));
+        int s = hip_status(ecs::launch_ecspmv(b, threads, lds, mask, (uint32_t)bits, stream));
         if (s) return s;
     }
     return ECSPMV_OK;

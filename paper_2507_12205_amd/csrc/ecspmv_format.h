@@ -15,6 +15,10 @@
 // 6.3.2 for 16-byte vectors) and holds halfs [8k, 8k+8) of that lane's run values[(4j+c)*g + r].
 // The unit of the residual set is a "lane unit": 16 consecutive elements of one row (16 delta bytes, 16 FP16
 // values); 64 lane units form a chunk that one wavefront decodes with a prefix scan over lane totals.
+//
+// Delta width (Section 6.2, EC-CSR-8 / EC-CSR-4 of Section 8.2): `delta_bits` of the image header is 8 or 4.
+// With 4 bits two deltas share a byte, the earlier one in the low nibble; a unit then has 32 delta bytes (2 per
+// lane), a lane unit 8 and a residual chunk 512; the largest delta is 15 and everything else is unchanged.
 #ifndef ECSPMV_FORMAT_H
 #define ECSPMV_FORMAT_H
 
@@ -26,7 +30,10 @@
 #define ECS_UNIT_COLS        64u         /* block columns per unit of a g >= 2 set */
 #define ECS_LANE_ELEMS       16u         /* residual elements per lane unit */
 #define ECS_CHUNK_LANES      64u         /* lane units per residual chunk */
-#define ECS_MAX_DELTA        255u        /* R_P - 1 for 8-bit deltas */
+#define ECS_MAX_DELTA(bits)  ((1u << (bits)) - 1u)   /* R_P - 1 */
+#define ECS_UNIT_DBYTES(bits)  (8u * (bits))        /* delta bytes of a 64-column unit */
+#define ECS_LANE_DBYTES(bits)  (2u * (bits))        /* delta bytes of a residual lane unit */
+#define ECS_CHUNK_DBYTES(bits) (128u * (bits))      /* delta bytes of a full residual chunk */
 #define ECS_NUM_BTYPES       4           /* t = 0..3  <->  g = 2, 4, 8, 16 */
 
 /* Words (uint32) of the panel header, which occupies the first ECS_PANEL_HEADER bytes of a panel. */
@@ -40,11 +47,11 @@ enum {
     PH_ROWSLOT_OFF = 5, /* byte offset in panel: uint16 first slot of each row, nrows + 1 entries */
     PH_RCHUNK_OFF = 6,  /* byte offset in panel: EcsRChunk per residual chunk */
     PH_RENTRY_OFF = 7,  /* byte offset in panel: EcsREntry per residual row segment */
-    PH_RD_OFF = 8,      /* byte offset in panel: residual deltas, 16 B per lane unit */
+    PH_RD_OFF = 8,      /* byte offset in panel: residual deltas, 16 B (8-bit) or 8 B (4-bit) per lane unit */
     PH_RV_OFF = 9,      /* byte offset in panel: residual values, 2 x 16 B per lane unit, chunk-wise [k][lane] */
     PH_NUNITS = 10,     /* +t: units of granularity 2 << t */
     PH_UTAB_OFF = 14,   /* +t: byte offset in panel: per unit (1 + g) uint16 = base column, g slots */
-    PH_BD_OFF = 18,     /* +t: byte offset in panel: 64 delta bytes per unit */
+    PH_BD_OFF = 18,     /* +t: byte offset in panel: 64 (8-bit) or 32 (4-bit) delta bytes per unit */
     PH_BV_OFF = 22,     /* +t: byte offset in panel: 128 * g value bytes per unit */
     PH_PANEL_BYTES = 26,
     PH_META_BYTES = 27
@@ -70,6 +77,7 @@ typedef struct EcsImageHeader {
     uint32_t panel_stride, meta_stride;
     uint32_t max_slots, lds_bytes;
     uint64_t image_bytes, nnz;
+    uint32_t delta_bits, reserved_;
 } EcsImageHeader;
 
 #endif

@@ -156,16 +156,17 @@ inline void list_bits(const std::vector<uint64_t> &bits, std::vector<int32_t> &o
     }
 }
 
-// Cut a sorted column list into units of 64 columns whose successive gaps fit an 8-bit delta (the
+// Cut a sorted column list into units of 64 columns whose successive gaps fit a delta index (the
 // "adjacent columns within the range R_P" rule of Section 6.2 and the "multiples of the load quantum" rule
 // of Section 6.3.1, with the quantum being one unit).  Columns that end up in no unit go to `rest`.
-void form_units(const std::vector<int32_t> &cols, std::vector<int32_t> &taken, std::vector<int32_t> &rest)
+void form_units(const std::vector<int32_t> &cols, int32_t max_delta, std::vector<int32_t> &taken,
+                std::vector<int32_t> &rest)
 {
     taken.clear();
     rest.clear();
     size_t start = 0;                 // start of the current candidate run inside cols
     for (size_t i = 0; i < cols.size(); ++i) {
-        if (i > start && cols[i] - cols[i - 1] > (int32_t)ECS_MAX_DELTA) {
+        if (i > start && cols[i] - cols[i - 1] > max_delta) {
             for (size_t k = start; k < i; ++k) rest.push_back(cols[k]);
             start = i;
         }
@@ -212,8 +213,9 @@ void row_matching(const std::vector<LRow> &rows, int nw, std::vector<std::pair<i
     }
 }
 
-void extract_panel(const Csr &A, int64_t row0, int nrows, int max_g, int max_rounds, PanelUnits &out)
+void extract_panel(const Csr &A, int64_t row0, int nrows, int max_g, int max_rounds, int delta_bits, PanelUnits &out)
 {
+    const int32_t max_delta = (int32_t)ECS_MAX_DELTA(delta_bits);
     const int n = (int)A.n;
     const int nw = (n + 63) / 64;
     std::vector<std::vector<LRow>> levels(1);
@@ -244,7 +246,7 @@ void extract_panel(const Csr &A, int64_t row0, int nrows, int max_g, int max_rou
                 LRow &a = AR[pr.first], &b = AR[pr.second];
                 for (int w = 0; w < nw; ++w) common[w] = a.bits[w] & b.bits[w];
                 list_bits(common, cols);
-                form_units(cols, taken, rest);
+                form_units(cols, max_delta, taken, rest);
                 if (taken.empty()) continue;
                 any = true;
                 LRow blk;
@@ -280,7 +282,7 @@ void extract_panel(const Csr &A, int64_t row0, int nrows, int max_g, int max_rou
         const int t = level - 1;
         for (LRow &L : rows) {
             list_bits(L.bits, cols);
-            form_units(cols, taken, rest);
+            form_units(cols, max_delta, taken, rest);
             for (int32_t c : rest) {
                 uint64_t bit = 1ull << (c & 63);
                 LRow &ca = levels[level - 1][L.child_a], &cb = levels[level - 1][L.child_b];
@@ -333,8 +335,23 @@ inline int hist_bin(unsigned d)
     return b;
 }
 
-void encode_panel(const Csr &A, int64_t row0, int nrows, PanelUnits &pu, bool reorder, PanelImage &img)
+// delta k of an array of `bits`-wide deltas; with 4 bits the earlier delta of a byte sits in its low nibble
+inline void put_delta(uint8_t *d, size_t k, int bits, uint32_t v)
 {
+    if (bits == 8)
+        d[k] = (uint8_t)v;
+    else
+        d[k >> 1] = (uint8_t)((k & 1) ? ((d[k >> 1] & 0x0F) | (v << 4)) : ((d[k >> 1] & 0xF0) | v));
+}
+inline uint32_t get_delta(const uint8_t *d, size_t k, int bits)
+{
+    return bits == 8 ? d[k] : ((d[k >> 1] >> (4 * (k & 1))) & 0xF);
+}
+
+void encode_panel(const Csr &A, int64_t row0, int nrows, PanelUnits &pu, bool reorder, int delta_bits, PanelImage &img)
+{
+    const int32_t max_delta = (int32_t)ECS_MAX_DELTA(delta_bits);
+    const uint32_t unit_db = ECS_UNIT_DBYTES(delta_bits), lane_db = ECS_LANE_DBYTES(delta_bits);
     // ---- ordering (Section 5): sets by decreasing granularity (fixed by the layout); inside a set the
     // units of longer blocks first.
     if (reorder)
@@ -361,10 +378,10 @@ void encode_panel(const Csr &A, int64_t row0, int nrows, PanelUnits &pu, bool re
         vs.push_back(value_at(A, row0 + r, cols[0]));
         for (size_t k = 1; k < cols.size(); ++k) {
             int32_t gap = cols[k] - cur;
-            while (gap > (int32_t)ECS_MAX_DELTA) {       // explicit zero every R_P - 1 columns (Section 6.2)
-                ds.push_back((uint8_t)ECS_MAX_DELTA);
+            while (gap > max_delta) {                    // explicit zero every R_P - 1 columns (Section 6.2)
+                ds.push_back((uint8_t)max_delta);
                 vs.push_back(0);
-                gap -= ECS_MAX_DELTA;
+                gap -= max_delta;
                 ++img.gap_pads;
                 ++img.pad_elements;
             }
@@ -464,19 +481,19 @@ void encode_panel(const Csr &A, int64_t row0, int nrows, PanelUnits &pu, bool re
         const uint32_t g = 2u << t;
         const uint32_t nu = (uint32_t)pu.units[t].size();
         hdr[PH_BD_OFF + t] = off;
-        off += 64u * nu;                  // multiple of 16
+        off += unit_db * nu;              // multiple of 16
         hdr[PH_BV_OFF + t] = off;
         off += 128u * g * nu;
-        img.delta_bytes += 64ll * nu;
+        img.delta_bytes += (int64_t)unit_db * nu;
         img.value_bytes += 128ll * g * nu;
         img.units_by_g[t + 1] = nu;
         img.nnz_by_g[t + 1] = (int64_t)nu * ECS_UNIT_COLS * g;
     }
     hdr[PH_RD_OFF] = off;
-    off += 16u * nlanes;
+    off = align_up(off + lane_db * nlanes, 16);
     hdr[PH_RV_OFF] = off;
     off += 32u * nlanes;
-    img.delta_bytes += 16ll * nlanes;
+    img.delta_bytes += (int64_t)lane_db * nlanes;
     img.value_bytes += 32ll * nlanes;
     off = align_up(off, 256);
     hdr[PH_PANEL_BYTES] = off;
@@ -493,9 +510,10 @@ void encode_panel(const Csr &A, int64_t row0, int nrows, PanelUnits &pu, bool re
             uint16_t *ue = utab + u * (1 + g);
             ue[0] = un.cols[0];
             for (uint32_t r = 0; r < g; ++r) ue[1 + r] = (uint16_t)cursor[un.rows[r]]++;
-            uint8_t *d = P + hdr[PH_BD_OFF + t] + 64u * u;
-            d[0] = 0;
-            for (unsigned k = 1; k < ECS_UNIT_COLS; ++k) d[k] = (uint8_t)(un.cols[k] - un.cols[k - 1]);
+            uint8_t *d = P + hdr[PH_BD_OFF + t] + unit_db * u;
+            put_delta(d, 0, delta_bits, 0);
+            for (unsigned k = 1; k < ECS_UNIT_COLS; ++k)
+                put_delta(d, k, delta_bits, (uint32_t)(un.cols[k] - un.cols[k - 1]));
             for (unsigned k = 0; k < ECS_UNIT_COLS; ++k)
                 for (uint32_t r = 0; r < g; ++r) flat[k * g + r] = value_at(A, row0 + un.rows[r], un.cols[k]);
             // permutation: lane j owns flat[4*j*g, 4*(j+1)*g); its k-th group of 8 halfs goes to k*128 + 8*j
@@ -509,11 +527,11 @@ void encode_panel(const Csr &A, int64_t row0, int nrows, PanelUnits &pu, bool re
     // ---- residual set
     for (uint32_t c = 0; c < nchunks; ++c) {
         const uint32_t nl = rchunks[c].nlanes;
-        uint8_t *d = P + hdr[PH_RD_OFF] + 1024u * c;
+        uint8_t *d = P + hdr[PH_RD_OFF] + ECS_CHUNK_DBYTES(delta_bits) * c;
         uint16_t *v = (uint16_t *)(P + hdr[PH_RV_OFF] + 2048u * c);
         for (uint32_t l = 0; l < nl; ++l) {
             const LaneUnit &lu = lanes[c * ECS_CHUNK_LANES + l];
-            std::memcpy(d + 16u * l, lu.d, 16);
+            for (uint32_t i = 0; i < ECS_LANE_ELEMS; ++i) put_delta(d + lane_db * l, i, delta_bits, lu.d[i]);
             for (uint32_t i = 0; i < 8; ++i) {
                 v[8 * l + i] = lu.v[i];                 // first 128-bit load of lane l
                 v[8 * nl + 8 * l + i] = lu.v[8 + i];    // second
@@ -578,8 +596,8 @@ int build_image(const Csr &A, const BuildParams &bp, Image &out)
     parallel_for(P, threads, [&](int64_t p) {
         const int64_t r0 = bound[p], r1 = (p + 1 == P) ? m : bound[p + 1];
         PanelUnits pu;
-        extract_panel(A, r0, (int)(r1 - r0), bp.max_granularity, bp.max_rounds, pu);
-        encode_panel(A, r0, (int)(r1 - r0), pu, bp.reorder, imgs[p]);
+        extract_panel(A, r0, (int)(r1 - r0), bp.max_granularity, bp.max_rounds, bp.delta_bits, pu);
+        encode_panel(A, r0, (int)(r1 - r0), pu, bp.reorder, bp.delta_bits, imgs[p]);
     });
     uint32_t stride = 256, meta = 16, slots = 1;
     for (auto &im : imgs) {
@@ -598,6 +616,7 @@ int build_image(const Csr &A, const BuildParams &bp, Image &out)
     out.nnz = nnz;
     out.num_panels = P;
     out.threads_per_wg = bp.threads_per_wg;
+    out.delta_bits = bp.delta_bits;
     out.panel_stride = stride;
     out.meta_stride = meta;
     out.max_slots = slots;
@@ -615,6 +634,7 @@ int build_image(const Csr &A, const BuildParams &bp, Image &out)
     st.csr16_bytes = 4 * nnz + 4 * (m + 1);
     st.num_panels = P;
     st.threads_per_wg = bp.threads_per_wg;
+    st.delta_bits = bp.delta_bits;
     st.panel_stride = stride;
     st.meta_stride = meta;
     st.lds_bytes = out.lds_bytes;
@@ -656,6 +676,7 @@ int build_image(const Csr &A, const BuildParams &bp, Image &out)
     ih.lds_bytes = out.lds_bytes;
     ih.image_bytes = total;
     ih.nnz = (uint64_t)nnz;
+    ih.delta_bits = (uint32_t)bp.delta_bits;
     std::memcpy(out.bytes.data(), &ih, sizeof(ih));
     st.build_seconds = std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count();
     return 0;
@@ -685,6 +706,7 @@ struct PanelView {
 int walk_image(const Image &im, Triples *tri, BlockSets *bs)
 {
     const uint8_t *base = im.bytes.data() + ECS_IMAGE_HEADER;
+    const int bits = im.delta_bits;
     for (int p = 0; p < im.num_panels; ++p) {
         PanelView pv;
         pv.P = base + (size_t)im.panel_stride * p;
@@ -697,7 +719,7 @@ int walk_image(const Image &im, Triples *tri, BlockSets *bs)
             const uint16_t *utab = (const uint16_t *)(pv.P + pv.hdr[PH_UTAB_OFF + t]);
             for (uint32_t u = 0; u < nu; ++u) {
                 const uint16_t *ue = utab + u * (1 + g);
-                const uint8_t *d = pv.P + pv.hdr[PH_BD_OFF + t] + 64u * u;
+                const uint8_t *d = pv.P + pv.hdr[PH_BD_OFF + t] + ECS_UNIT_DBYTES(bits) * u;
                 const uint16_t *v = (const uint16_t *)(pv.P + pv.hdr[PH_BV_OFF + t] + 128u * g * u);
                 int32_t cols[ECS_UNIT_COLS];
                 // 16 lanes x 4 columns: local prefix inside a lane, exclusive scan over lanes, plus base
@@ -705,7 +727,7 @@ int walk_image(const Image &im, Triples *tri, BlockSets *bs)
                 for (uint32_t j = 0; j < 16; ++j) {
                     uint32_t rel = 0;
                     for (uint32_t c = 0; c < 4; ++c) {
-                        rel += d[4 * j + c];
+                        rel += get_delta(d, 4 * j + c, bits);
                         cols[4 * j + c] = (int32_t)(ue[0] + lane_excl + rel);
                     }
                     lane_excl += rel;
@@ -742,7 +764,7 @@ int walk_image(const Image &im, Triples *tri, BlockSets *bs)
         for (uint32_t c = 0; c < nchunks; ++c) {
             const uint32_t nl = std::min<uint32_t>(ECS_CHUNK_LANES, nlanes - c * ECS_CHUNK_LANES);
             if (rch[c].nlanes != nl || !(rch[c].head_mask & 1)) return -101;
-            const uint8_t *d = pv.P + pv.hdr[PH_RD_OFF] + 1024u * c;
+            const uint8_t *d = pv.P + pv.hdr[PH_RD_OFF] + ECS_CHUNK_DBYTES(bits) * c;
             const uint16_t *v = (const uint16_t *)(pv.P + pv.hdr[PH_RV_OFF] + 2048u * c);
             int64_t excl = 0;
             for (uint32_t l = 0; l < nl; ++l) {
@@ -752,7 +774,7 @@ int walk_image(const Image &im, Triples *tri, BlockSets *bs)
                 if (row != (int)e.row_local) return -102;
                 int64_t rel = 0;
                 for (uint32_t k = 0; k < ECS_LANE_ELEMS; ++k) {
-                    rel += d[16 * l + k];
+                    rel += get_delta(d + ECS_LANE_DBYTES(bits) * l, k, bits);
                     const uint16_t val = (k < 8) ? v[8 * l + k] : v[8 * nl + 8 * l + (k - 8)];
                     if ((val & 0x7FFF) == 0) continue;
                     tri->rows.push_back((int32_t)(row0 + row));

@@ -18,6 +18,7 @@ struct Csr {
 };
 
 struct BuildParams {
+    int delta_bits = 8;
     int max_granularity = 8;
     int max_rounds = 64;
     int num_panels = 0;
@@ -30,7 +31,7 @@ struct BuildParams {
 struct Image {
     std::vector<uint8_t> bytes;
     int64_t m = 0, n = 0, nnz = 0;
-    int num_panels = 0, threads_per_wg = 1024;
+    int num_panels = 0, threads_per_wg = 1024, delta_bits = 8;
     uint32_t panel_stride = 0, meta_stride = 0, max_slots = 0, lds_bytes = 0;
     uint32_t type_mask = 0;   // bit t set: some panel holds units of granularity 2 << t
     ecspmv_stats_t stats;

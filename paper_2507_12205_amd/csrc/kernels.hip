@@ -116,6 +116,18 @@ __device__ __forceinline__ uint32_t load4(const uint8_t *p)
     return __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(p));
 }
 
+__device__ __forceinline__ uint32_t load2(const uint8_t *p)
+{
+    return __builtin_nontemporal_load(reinterpret_cast<const uint16_t *>(p));
+}
+
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint2 load8(const uint8_t *p)
+{
+    const u32x2 t = __builtin_nontemporal_load(reinterpret_cast<const u32x2 *>(p));
+    return make_uint2(t.x, t.y);
+}
+
 struct Ctx {
     const uint8_t *panel;      // global
     const uint16_t *xs;        // LDS: x as FP16 bits
@@ -125,30 +137,33 @@ struct Ctx {
 };
 
 // ---- g >= 2 block sets: a DPP row of 16 lanes takes one unit (64 columns), 4 columns per lane; a wavefront
-// takes a chunk of 4 consecutive units.
+// takes a chunk of 4 consecutive units.  DB = width of a delta index in bits (8 or 4).
 template <int G>
 struct UnitRegs {
-    uint32_t d;            // 4 delta bytes
+    uint32_t d;            // 4 deltas: 4 bytes, or 4 nibbles in the low half
     uint4 v[G / 2];        // 4 * G FP16 values of this lane
 };
 
 // Unconditional: DPP rows beyond the last unit of the set re-read that last unit (and ignore it), so that the
 // number of loads in flight never depends on data and waits can name exact counts.
-template <int G>
+template <int G, int DB>
 __device__ __forceinline__ void load_unit(const Ctx &c, uint32_t bd_off, uint32_t bv_off, uint32_t u, uint32_t nu,
                                           UnitRegs<G> &r)
 {
     const uint32_t j = c.lane & 15;
     const uint32_t uu = min(u, nu - 1u);
     // one 32-bit offset from the (wave-uniform) panel pointer per load: scalar base + vector offset addressing
-    const uint32_t od = bd_off + 64u * uu + 4u * j;
+    const uint32_t od = bd_off + (8u * DB) * uu + (DB / 2u) * j;
     const uint32_t ov = bv_off + (128u * G) * uu + 16u * j;
-    r.d = load4(c.panel + od);
+    if constexpr (DB == 8)
+        r.d = load4(c.panel + od);
+    else
+        r.d = load2(c.panel + od);
 #pragma unroll
     for (int k = 0; k < G / 2; ++k) r.v[k] = load16(c.panel + (ov + 256u * k));
 }
 
-template <int G>
+template <int G, int DB>
 __device__ __forceinline__ void compute_unit(const Ctx &c, const uint16_t *utab, uint32_t u, uint32_t nu,
                                              const UnitRegs<G> &r)
 {
@@ -157,10 +172,11 @@ __device__ __forceinline__ void compute_unit(const Ctx &c, const uint16_t *utab,
     const uint32_t uu = min(u, nu - 1u);
     // delta decode: local prefix over the lane's 4 columns, exclusive scan over the 16 lanes, unit base
     uint32_t rel[4];
-    rel[0] = r.d & 0xFF;
-    rel[1] = rel[0] + ((r.d >> 8) & 0xFF);
-    rel[2] = rel[1] + ((r.d >> 16) & 0xFF);
-    rel[3] = rel[2] + (r.d >> 24);
+    constexpr uint32_t DM = (1u << DB) - 1u;
+    rel[0] = r.d & DM;
+    rel[1] = rel[0] + ((r.d >> DB) & DM);
+    rel[2] = rel[1] + ((r.d >> (2 * DB)) & DM);
+    rel[3] = rel[2] + ((r.d >> (3 * DB)) & DM);
     const int incl = row16_incl_scan((int)rel[3]);
     const uint16_t *ue = utab + uu * (1 + G);
     const uint32_t start = (uint32_t)ue[0] + (uint32_t)incl - rel[3];
@@ -188,7 +204,7 @@ __device__ __forceinline__ void compute_unit(const Ctx &c, const uint16_t *utab,
 // A set's chunks c0, c0 + W, c0 + 2W, ... belong to this wavefront.  DEPTH register buffers take turns: all are
 // requested before anything is computed, and each is refilled right after it has been consumed, so a wavefront
 // always has its next DEPTH chunks on the way (the double buffering of Section 7, deeper and without copies).
-template <int G, int DEPTH>
+template <int G, int DB, int DEPTH>
 struct BlockSet {
     UnitRegs<G> buf[DEPTH];
     uint32_t nu, n, c0, bd_off, bv_off;
@@ -213,7 +229,7 @@ struct BlockSet {
 #pragma unroll
         for (int d = 0; d < DEPTH; ++d) {
             const bool have = (uint32_t)d < n;
-            load_unit<G>(c, have ? bd_off : 0u, have ? bv_off : 0u, have ? unit_of(c, d) : 0u, have ? nu : 1u, buf[d]);
+            load_unit<G, DB>(c, have ? bd_off : 0u, have ? bv_off : 0u, have ? unit_of(c, d) : 0u, have ? nu : 1u, buf[d]);
         }
     }
     __device__ __forceinline__ void run(const Ctx &c)
@@ -222,53 +238,65 @@ struct BlockSet {
         for (; i + 2 * DEPTH - 1 < n; i += DEPTH) {    // chunks i + DEPTH ... i + 2 DEPTH - 1 exist: unconditional refills
 #pragma unroll
             for (int d = 0; d < DEPTH; ++d) {
-                compute_unit<G>(c, utab, unit_of(c, i + d), nu, buf[d]);
-                load_unit<G>(c, bd_off, bv_off, unit_of(c, i + DEPTH + d), nu, buf[d]);
+                compute_unit<G, DB>(c, utab, unit_of(c, i + d), nu, buf[d]);
+                load_unit<G, DB>(c, bd_off, bv_off, unit_of(c, i + DEPTH + d), nu, buf[d]);
             }
         }
 #pragma unroll
         for (int d = 0; d < DEPTH; ++d) {
             if (i + d < n) {
-                compute_unit<G>(c, utab, unit_of(c, i + d), nu, buf[d]);
-                if (i + DEPTH + d < n) load_unit<G>(c, bd_off, bv_off, unit_of(c, i + DEPTH + d), nu, buf[d]);
+                compute_unit<G, DB>(c, utab, unit_of(c, i + d), nu, buf[d]);
+                if (i + DEPTH + d < n) load_unit<G, DB>(c, bd_off, bv_off, unit_of(c, i + DEPTH + d), nu, buf[d]);
             }
         }
 #pragma unroll
         for (int d = 0; d < DEPTH; ++d)
-            if (i + DEPTH + d < n) compute_unit<G>(c, utab, unit_of(c, i + DEPTH + d), nu, buf[d]);
+            if (i + DEPTH + d < n) compute_unit<G, DB>(c, utab, unit_of(c, i + DEPTH + d), nu, buf[d]);
     }
 };
 
 // ---- residual (1-grained) set: a wavefront takes a chunk of 64 lane units, 16 elements per lane.
+template <int DB>
 struct ChunkRegs {
-    uint4 d;      // 16 delta bytes
-    uint4 v0, v1; // 16 FP16 values
+    uint32_t d[DB / 2]; // 16 deltas: 16 bytes or 16 nibbles
+    uint4 v0, v1;       // 16 FP16 values
 };
 
+template <int DB>
 __device__ __forceinline__ void load_chunk(const Ctx &c, uint32_t rd_off, uint32_t rv_off, uint32_t ch, uint32_t nlanes,
-                                           ChunkRegs &r)
+                                           ChunkRegs<DB> &r)
 {
     const uint32_t nl = min(64u, nlanes - 64u * ch);
     const uint32_t ll = min(c.lane, nl - 1u);           // lanes beyond the chunk's end re-read its last lane unit
-    const uint32_t od = rd_off + 1024u * ch + 16u * ll;
+    const uint32_t od = rd_off + (128u * DB) * ch + (2u * DB) * ll;
     const uint32_t ov = rv_off + 2048u * ch + 16u * ll;
-    r.d = load16(c.panel + od);
+    if constexpr (DB == 8) {
+        const uint4 t = load16(c.panel + od);
+        r.d[0] = t.x, r.d[1] = t.y, r.d[2] = t.z, r.d[3] = t.w;
+    } else {
+        const uint2 t = load8(c.panel + od);
+        r.d[0] = t.x, r.d[1] = t.y;
+    }
     r.v0 = load16(c.panel + ov);
     r.v1 = load16(c.panel + (ov + 16u * nl));
 }
 
+template <int DB>
 __device__ __forceinline__ void compute_chunk(const Ctx &c, const EcsRChunk *rch, const EcsREntry *ren, uint32_t ch,
-                                              uint32_t nlanes, const ChunkRegs &r)
+                                              uint32_t nlanes, const ChunkRegs<DB> &r)
 {
     const uint32_t nl = min(64u, nlanes - 64u * ch);
     const bool active = c.lane < nl;
     // lane-local inclusive prefix of the 16 deltas
     uint32_t rel[16];
-    const uint32_t dw[4] = {active ? r.d.x : 0u, active ? r.d.y : 0u, active ? r.d.z : 0u, active ? r.d.w : 0u};
+    constexpr int PER = 32 / DB;                  // deltas per 32-bit word
+    uint32_t dw[DB / 2];
+#pragma unroll
+    for (int w = 0; w < DB / 2; ++w) dw[w] = active ? r.d[w] : 0u;
     uint32_t run = 0;
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
-        run += (dw[i >> 2] >> (8 * (i & 3))) & 0xFF;
+        run += (dw[i / PER] >> (DB * (i % PER))) & ((1u << DB) - 1u);
         rel[i] = run;
     }
     // wave64 prefix scan of the lane totals; the segment's entry folds base column and earlier lanes
@@ -294,9 +322,9 @@ __device__ __forceinline__ void compute_chunk(const Ctx &c, const EcsRChunk *rch
     if (is_end) c.slots[e.slot] = seg_sum;
 }
 
-template <int DEPTH>
+template <int DB, int DEPTH>
 struct ResidualSet {
-    ChunkRegs buf[DEPTH];
+    ChunkRegs<DB> buf[DEPTH];
     uint32_t nlanes, n, c0, rd_off, rv_off;
     const EcsRChunk *rch;
     const EcsREntry *ren;
@@ -316,7 +344,7 @@ struct ResidualSet {
 #pragma unroll
         for (int d = 0; d < DEPTH; ++d) {
             const bool have = (uint32_t)d < n;
-            load_chunk(c, have ? rd_off : 0u, have ? rv_off : 0u, have ? chunk_of(c, d) : 0u, have ? nlanes : 1u, buf[d]);
+            load_chunk<DB>(c, have ? rd_off : 0u, have ? rv_off : 0u, have ? chunk_of(c, d) : 0u, have ? nlanes : 1u, buf[d]);
         }
     }
     __device__ __forceinline__ void run(const Ctx &c)
@@ -325,25 +353,26 @@ struct ResidualSet {
         for (; i + 2 * DEPTH - 1 < n; i += DEPTH) {
 #pragma unroll
             for (int d = 0; d < DEPTH; ++d) {
-                compute_chunk(c, rch, ren, chunk_of(c, i + d), nlanes, buf[d]);
-                load_chunk(c, rd_off, rv_off, chunk_of(c, i + DEPTH + d), nlanes, buf[d]);
+                compute_chunk<DB>(c, rch, ren, chunk_of(c, i + d), nlanes, buf[d]);
+                load_chunk<DB>(c, rd_off, rv_off, chunk_of(c, i + DEPTH + d), nlanes, buf[d]);
             }
         }
 #pragma unroll
         for (int d = 0; d < DEPTH; ++d) {
             if (i + d < n) {
-                compute_chunk(c, rch, ren, chunk_of(c, i + d), nlanes, buf[d]);
-                if (i + DEPTH + d < n) load_chunk(c, rd_off, rv_off, chunk_of(c, i + DEPTH + d), nlanes, buf[d]);
+                compute_chunk<DB>(c, rch, ren, chunk_of(c, i + d), nlanes, buf[d]);
+                if (i + DEPTH + d < n) load_chunk<DB>(c, rd_off, rv_off, chunk_of(c, i + DEPTH + d), nlanes, buf[d]);
             }
         }
 #pragma unroll
         for (int d = 0; d < DEPTH; ++d)
-            if (i + DEPTH + d < n) compute_chunk(c, rch, ren, chunk_of(c, i + DEPTH + d), nlanes, buf[d]);
+            if (i + DEPTH + d < n) compute_chunk<DB>(c, rch, ren, chunk_of(c, i + DEPTH + d), nlanes, buf[d]);
     }
 };
 
-// TM: bit t set = the image holds units of granularity 2 << t somewhere (the residual set is always handled)
-template <int TM>
+// TM: bit t set = the image holds units of granularity 2 << t somewhere (the residual set is always handled);
+// DB: width of the delta indices in bits
+template <int TM, int DB>
 __global__ __launch_bounds__(1024) void ecspmv_kernel(const ecs::EcsBatch batch)
 {
     // which SpMV of the batch this workgroup works for (one item in the plain case)
@@ -396,11 +425,11 @@ __global__ __launch_bounds__(1024) void ecspmv_kernel(const ecs::EcsBatch batch)
     for (int w = 0; w < (int)(ECS_PANEL_HEADER / 4); ++w) hdr[w] = (uint32_t)__builtin_amdgcn_readlane((int)hword, w);
     // buffers per set: deeper where chunks are small and frequent, shallower where registers run out
     constexpr bool wide = (TM & 12) != 0;
-    BlockSet<16, 1> b16;
-    BlockSet<8, 1> b8;
-    BlockSet<4, wide ? 1 : D4> b4;
-    BlockSet<2, wide ? 2 : D2> b2;
-    ResidualSet<wide ? 2 : DR> rs;
+    BlockSet<16, DB, 1> b16;
+    BlockSet<8, DB, 1> b8;
+    BlockSet<4, DB, wide ? 1 : D4> b4;
+    BlockSet<2, DB, wide ? 2 : D2> b2;
+    ResidualSet<DB, wide ? 2 : DR> rs;
     if constexpr ((TM & 8) != 0) b16.prologue(c, hdr, 3);
     if constexpr ((TM & 4) != 0) b8.prologue(c, hdr, 2);
     if constexpr ((TM & 2) != 0) b4.prologue(c, hdr, 1);
@@ -490,31 +519,39 @@ __global__ __launch_bounds__(1024) void stream_read_kernel(const uint4 *__restri
 
 namespace ecs {
 
-template <int TM>
-static int launch_tm(const EcsBatch &batch, uint32_t threads, uint32_t lds_bytes, void *stream)
+template <int TM, int DB>
+static int launch_k(const EcsBatch &batch, uint32_t threads, uint32_t lds_bytes, void *stream)
 {
     static thread_local uint32_t attr_set_for = 0;
     if (lds_bytes > 65536 && lds_bytes > attr_set_for) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(ecspmv_kernel<TM>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(ecspmv_kernel<TM, DB>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
         if (e != hipSuccess) return (int)e;
         attr_set_for = lds_bytes;
     }
     const uint32_t grid = batch.item[batch.count - 1].block_end;
-    hipLaunchKernelGGL(ecspmv_kernel<TM>, dim3(grid), dim3(threads), lds_bytes, (hipStream_t)stream, batch);
+    hipLaunchKernelGGL((ecspmv_kernel<TM, DB>), dim3(grid), dim3(threads), lds_bytes, (hipStream_t)stream, batch);
     return (int)hipGetLastError();
 }
 
-int launch_ecspmv(const EcsBatch &batch, uint32_t threads, uint32_t lds_bytes, uint32_t type_mask, void *stream)
+template <int TM>
+static int launch_tm(const EcsBatch &batch, uint32_t threads, uint32_t lds_bytes, uint32_t delta_bits, void *stream)
+{
+    return delta_bits == 4 ? launch_k<TM, 4>(batch, threads, lds_bytes, stream)
+                           : launch_k<TM, 8>(batch, threads, lds_bytes, stream);
+}
+
+int launch_ecspmv(const EcsBatch &batch, uint32_t threads, uint32_t lds_bytes, uint32_t type_mask, uint32_t delta_bits,
+                  void *stream)
 {
     // one instantiation per highest granularity present: sets that do not occur cost no registers
     const int top = (type_mask & 8) ? 15 : (type_mask & 4) ? 7 : (type_mask & 2) ? 3 : (type_mask & 1) ? 1 : 0;
     switch (top) {
-    case 15: return launch_tm<15>(batch, threads, lds_bytes, stream);
-    case 7: return launch_tm<7>(batch, threads, lds_bytes, stream);
-    case 3: return launch_tm<3>(batch, threads, lds_bytes, stream);
-    case 1: return launch_tm<1>(batch, threads, lds_bytes, stream);
-    default: return launch_tm<0>(batch, threads, lds_bytes, stream);
+    case 15: return launch_tm<15>(batch, threads, lds_bytes, delta_bits, stream);
+    case 7: return launch_tm<7>(batch, threads, lds_bytes, delta_bits, stream);
+    case 3: return launch_tm<3>(batch, threads, lds_bytes, delta_bits, stream);
+    case 1: return launch_tm<1>(batch, threads, lds_bytes, delta_bits, stream);
+    default: return launch_tm<0>(batch, threads, lds_bytes, delta_bits, stream);
     }
 }
 

@@ -22,7 +22,8 @@ struct EcsBatch {
 };
 
 // Launches one kernel for all items (count <= ECS_MAX_BATCH, same workgroup size for all).
-int launch_ecspmv(const EcsBatch &batch, uint32_t threads, uint32_t lds_bytes, uint32_t type_mask, void *stream);
+int launch_ecspmv(const EcsBatch &batch, uint32_t threads, uint32_t lds_bytes, uint32_t type_mask, uint32_t delta_bits,
+                  void *stream);
 int launch_csr(const void *d_rowptr, const void *d_col, const void *d_val, const void *d_x, void *d_y, uint32_t m,
                void *stream);
 int launch_stream_read(const void *d_buf, uint64_t bytes, void *d_out, uint32_t num_wg, void *stream);

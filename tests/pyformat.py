@@ -1,6 +1,6 @@
 """Independent Python reading of the EC-CSR device image (layout as documented in csrc/ecspmv_format.h).
 
-Used by the tests only: it re-derives columns from bases and 8-bit deltas with the recurrence
+Used by the tests only: it re-derives columns from bases and 8- or 4-bit deltas with the recurrence
 I_k = I_0 + sum_{i<=k} dI_i (paper Section 6.2) and undoes the value permutation of Section 6.3.2, without
 calling the library's own decoder.
 """
@@ -12,11 +12,21 @@ PH = dict(ROW0=0, NROWS=1, NSLOTS=2, NRLANES=3, NRENTRIES=4, ROWSLOT_OFF=5, RCHU
 
 
 def image_header(img: np.ndarray) -> dict:
-    w = img[:48].view(np.uint32)
+    w = img[:64].view(np.uint32)
     q = img[40:56].view(np.uint64)
     return dict(magic=int(w[0]), version=int(w[1]), m=int(w[2]), n=int(w[3]), num_panels=int(w[4]),
                 threads_per_wg=int(w[5]), panel_stride=int(w[6]), meta_stride=int(w[7]), max_slots=int(w[8]),
-                lds_bytes=int(w[9]), image_bytes=int(q[0]), nnz=int(q[1]))
+                lds_bytes=int(w[9]), image_bytes=int(q[0]), nnz=int(q[1]), delta_bits=int(w[14]))
+
+
+def deltas_of(raw: np.ndarray, bits: int) -> np.ndarray:
+    """The delta indices held in `raw` bytes: one per byte, or two per byte with the earlier one in the low nibble."""
+    if bits == 8:
+        return raw.astype(np.int64)
+    out = np.empty(2 * len(raw), dtype=np.int64)
+    out[0::2] = raw & 0x0F
+    out[1::2] = raw >> 4
+    return out
 
 
 def walk(img: np.ndarray):
@@ -25,6 +35,9 @@ def walk(img: np.ndarray):
     kind 'block': g, rows (g,), cols (64,), deltas (64,), base, values (64, g) uint16
     kind 'lane':  row, cols (16,), deltas (16,), values (16,) uint16, first_of_row (bool)"""
     ih = image_header(img)
+    bits = ih["delta_bits"]
+    assert bits in (4, 8)
+    udb, ldb, cdb = 8 * bits, 2 * bits, 128 * bits           # delta bytes per unit, lane unit, full residual chunk
     for p in range(ih["num_panels"]):
         P = img[IMAGE_HEADER + p * ih["panel_stride"]: IMAGE_HEADER + (p + 1) * ih["panel_stride"]]
         hdr = P[:128].view(np.uint32)
@@ -41,7 +54,7 @@ def walk(img: np.ndarray):
             ut, bd, bv = int(hdr[PH["UTAB_OFF"] + t]), int(hdr[PH["BD_OFF"] + t]), int(hdr[PH["BV_OFF"] + t])
             for u in range(nu):
                 ue = P[ut + 2 * (1 + g) * u: ut + 2 * (1 + g) * (u + 1)].view(np.uint16)
-                d = P[bd + 64 * u: bd + 64 * (u + 1)].astype(np.int64)
+                d = deltas_of(P[bd + udb * u: bd + udb * (u + 1)], bits)
                 cols = int(ue[0]) + np.cumsum(d)                       # I_k = I_0 + sum of deltas
                 raw = P[bv + 128 * g * u: bv + 128 * g * (u + 1)].view(np.uint16)
                 flat = np.empty(64 * g, dtype=np.uint16)               # undo: k-th 8-half group of lane j at k*128 + 8j
@@ -65,7 +78,7 @@ def walk(img: np.ndarray):
                 e = P[re_ + 8 * (entry0 + seg): re_ + 8 * (entry0 + seg + 1)]
                 cc = int(e[:4].view(np.int32)[0])
                 slot, row_local = (int(v) for v in e[4:8].view(np.uint16))
-                d = P[rd + 1024 * c + 16 * l: rd + 1024 * c + 16 * (l + 1)].astype(np.int64)
+                d = deltas_of(P[rd + cdb * c + ldb * l: rd + cdb * c + ldb * (l + 1)], bits)
                 v0 = P[rv + 2048 * c + 16 * l: rv + 2048 * c + 16 * (l + 1)].view(np.uint16)
                 v1 = P[rv + 2048 * c + 16 * nl + 16 * l: rv + 2048 * c + 16 * nl + 16 * (l + 1)].view(np.uint16)
                 cols = cc + excl + np.cumsum(d)

@@ -1,0 +1,208 @@
+"""EC-CSR-4 (4-bit delta indices, paper Sections 6.2 and 8.2) on the host: packing, the 15-column filler rule,
+what may become a block, byte accounting, round trip, and parity of the extraction with the oracle's."""
+import numpy as np
+import pytest
+
+import paper_2507_12205_amd as E
+from paper_2507_12205_amd import binding as B
+from oracle import extraction_oracle as xo
+from oracle import oracle as orc
+from workloads import generators as gen
+
+import pyformat
+
+
+def roundtrip_ok(A, W):
+    r, c, v = A.ecspmv_decode()
+    rr, cc, vv = orc.pattern_triples(W)
+    o = np.lexsort((c, r))
+    return np.array_equal(r[o], rr) and np.array_equal(c[o], cc) and np.array_equal(v[o], vv)
+
+
+def test_only_widths_4_and_8_are_built():
+    W = gen.small_random(20, 100, 0.3, 1)[0]
+    for bits in (1, 2, 5, 16):
+        with pytest.raises(E.EcspmvError) as e:
+            E.ecspmv_build_dense(W, E.make_opts(delta_bits=bits))
+        assert e.value.status == B.ERR_UNSUPPORTED
+    assert E.ecspmv_build_dense(W, E.make_opts(delta_bits=4)).ecspmv_stats().delta_bits == 4
+    assert E.ecspmv_build_dense(W, E.make_opts(delta_bits=8)).ecspmv_stats().delta_bits == 8
+    assert E.ecspmv_build_dense(W).ecspmv_stats().delta_bits == 8
+
+
+@pytest.mark.parametrize("cid,div", [(0, 1), (1, 4), (2, 8), (3, 4), (4, 8)])
+def test_roundtrip_bit_exact_on_the_configs(cid, div):
+    cfg = gen.scaled(gen.config(cid), div) if div > 1 else gen.config(cid)
+    for sid in range(len(cfg.shapes)):
+        if cid == 3 and sid in (1, 2, 3, 5):
+            continue
+        W = gen.make_matrix(cfg, sid)
+        A = E.ecspmv_build_dense(W, E.make_opts(delta_bits=4))
+        assert roundtrip_ok(A, W), (cid, sid)
+        st = A.ecspmv_stats()
+        assert sum(st.nnz_by_g) == st.nnz == int(np.count_nonzero(W.view(np.uint16) & 0x7FFF))
+
+
+@pytest.mark.parametrize("opts", [dict(max_granularity=1), dict(max_granularity=16), dict(num_panels=1),
+                                  dict(num_panels=7, threads_per_wg=256), dict(flags=B.FLAG_GLOBAL_MATCHING)])
+def test_roundtrip_under_options(opts):
+    W = gen.make_matrix(gen.scaled(gen.config(1), 8), 0)
+    A = E.ecspmv_build_dense(W, E.make_opts(delta_bits=4, **opts))
+    assert roundtrip_ok(A, W)
+
+
+def test_roundtrip_edge_shapes():
+    cases = [np.zeros((5, 9), dtype=np.float16), np.ones((1, 1), dtype=np.float16),
+             gen.small_random(1, 3000, 0.5, 1)[0], gen.small_random(300, 1, 0.5, 2)[0],
+             gen.small_random(64, 6000, 0.001, 3)[0], gen.small_random(33, 1000, 1.5, 4)[0]]
+    W = np.zeros((3, 600), dtype=np.float16)
+    W[0, [0, 599]] = 1.0                                                        # one gap of 599 columns: 39 fillers
+    W[2, 300] = -2.0
+    cases.append(W)
+    for W in cases:
+        A = E.ecspmv_build_dense(W, E.make_opts(delta_bits=4))
+        assert roundtrip_ok(A, W), W.shape
+
+
+def test_python_reading_of_the_image_agrees_and_deltas_fit_four_bits():
+    W = gen.make_matrix(gen.scaled(gen.config(1), 8), 0)
+    A = E.ecspmv_build_dense(W, E.make_opts(delta_bits=4))
+    img = A.ecspmv_export_image()
+    assert pyformat.image_header(img)["delta_bits"] == 4
+    r, c, v = pyformat.triples(img)
+    rr, cc, vv = orc.pattern_triples(W)
+    assert np.array_equal(r, rr) and np.array_equal(c, cc) and np.array_equal(v, vv)
+    kinds = set()
+    bits = W.view(np.uint16)
+    for u in pyformat.walk(img):
+        kinds.add(u["kind"])
+        assert 0 <= u["deltas"].min() and u["deltas"].max() <= 15
+        if u["kind"] == "block":
+            assert u["deltas"][0] == 0 and u["cols"][0] == u["base"] and np.all(np.diff(u["cols"]) > 0)
+            for k, row in enumerate(u["rows"]):
+                assert np.array_equal(bits[row, u["cols"]], u["values"][:, k])
+    assert kinds == {"block", "lane"}                       # at density 0.5 two rows share runs of 64 close columns
+
+
+def test_two_deltas_per_byte_low_nibble_first():
+    """The worked example of Section 6.2 (base 2, deltas 0 2 1 1 for columns 2 4 5 6) with 4-bit deltas: the unit's
+    first two delta bytes are 0x20 and 0x11."""
+    cols = np.array([2, 4, 5, 6] + list(range(8, 128, 2)))
+    assert len(cols) == 64
+    W = np.zeros((2, 200), dtype=np.float16)
+    W[:, cols] = np.arange(1, 129, dtype=np.float16).reshape(2, 64)
+    A = E.ecspmv_build_dense(W, E.make_opts(num_panels=1, delta_bits=4))
+    img = A.ecspmv_export_image()
+    units = list(pyformat.walk(img))
+    assert len(units) == 1 and units[0]["kind"] == "block" and units[0]["g"] == 2
+    u = units[0]
+    assert u["base"] == 2 and u["deltas"][:4].tolist() == [0, 2, 1, 1] and u["cols"].tolist() == cols.tolist()
+    hdr = img[256:256 + 128].view(np.uint32)
+    bd = 256 + int(hdr[pyformat.PH["BD_OFF"] + 0])
+    assert img[bd:bd + 3].tolist() == [0x20, 0x11, 0x22]
+    st = A.ecspmv_stats()
+    assert st.delta_bytes == 32 and st.value_bytes == 256
+    assert np.array_equal(u["values"].T, W[:, cols].view(np.uint16))
+
+
+def test_fillers_every_fifteen_columns():
+    """Section 6.2 with R_P = 16: across a gap wider than 15 columns an explicit zero is stored every 15 columns."""
+    W = np.zeros((1, 200), dtype=np.float16)
+    W[0, [10, 11, 50, 66, 81]] = [1, 2, 3, 4, 5]
+    A = E.ecspmv_build_dense(W, E.make_opts(delta_bits=4))
+    st = A.ecspmv_stats()
+    # 11 -> 50: 39 = 15 + 15 + 9 (2 fillers); 50 -> 66: 16 = 15 + 1 (1 filler); 66 -> 81: 15 fits
+    assert st.gap_pad_elements == 3 and st.pad_elements == 3 + 8
+    lanes = list(pyformat.walk(A.ecspmv_export_image()))
+    assert len(lanes) == 1
+    d, v = lanes[0]["deltas"], lanes[0]["values"]
+    assert d[:8].tolist() == [0, 1, 15, 15, 9, 15, 1, 15]
+    assert lanes[0]["cols"][:8].tolist() == [10, 11, 26, 41, 50, 65, 66, 81]
+    assert np.all(v[[2, 3, 5]] == 0) and np.all(d[8:] == 0) and np.all(v[8:] == 0)
+    assert st.delta_bytes == 8 and st.value_bytes == 32
+    assert roundtrip_ok(A, W)
+
+
+def test_a_gap_of_sixteen_breaks_a_unit_only_with_four_bits():
+    W = np.zeros((2, 2100), dtype=np.float16)
+    W[:, np.arange(0, 64 * 16, 16)] = 1.0                   # 64 shared columns, 16 apart
+    W[:, 1100 + np.arange(0, 64 * 15, 15)] = 2.0            # 64 shared columns, 15 apart
+    a8 = E.ecspmv_build_dense(W, E.make_opts(num_panels=1, delta_bits=8)).ecspmv_stats()
+    a4 = E.ecspmv_build_dense(W, E.make_opts(num_panels=1, delta_bits=4))
+    s4 = a4.ecspmv_stats()
+    assert a8.nnz_by_g[1] == 256 and a8.nnz_by_g[0] == 0
+    assert s4.nnz_by_g[1] == 128 and s4.nnz_by_g[0] == 128
+    g, rows, cols = a4.ecspmv_block_sets()
+    assert g.tolist() == [2] and cols[0].tolist() == (1100 + np.arange(0, 64 * 15, 15)).tolist()
+    assert s4.gap_pad_elements == 2 * 63                    # the 16-apart run: one filler per gap, in both rows
+    assert roundtrip_ok(a4, W)
+
+
+def test_byte_accounting():
+    W = gen.make_matrix(gen.scaled(gen.config(3), 4), 0)
+    nnz = int(np.count_nonzero(W))
+    A = E.ecspmv_build_dense(W, E.make_opts(max_granularity=1, delta_bits=4))
+    st = A.ecspmv_stats()
+    stored = nnz + st.pad_elements
+    assert st.value_bytes == 2 * stored and 2 * st.delta_bytes == stored
+    assert st.image_bytes == st.value_bytes + st.delta_bytes + st.meta_bytes + st.slack_bytes
+    assert st.delta_hist[5] + st.delta_hist[6] + st.delta_hist[7] + st.delta_hist[8] == 0      # no delta above 15
+    a8 = E.ecspmv_build_dense(W, E.make_opts(max_granularity=1, delta_bits=8)).ecspmv_stats()
+    assert st.gap_pad_elements > a8.gap_pad_elements == 0
+    assert st.image_bytes < 0.9 * a8.image_bytes            # 2.5 against 3 bytes per element, a few fillers more
+    assert 0.41 < st.image_bytes / st.csr32_bytes < 0.48            # small matrix: tables and slack weigh more
+
+
+# ---- extraction parity with the oracle at delta range 15 ------------------------------------------------------
+
+def library_block_sets(A):
+    g, rows, cols = A.ecspmv_block_sets()
+    out, p = {}, 0
+    for u in range(len(g)):
+        out.setdefault(int(g[u]), []).append((tuple(int(v) for v in rows[p:p + g[u]]), tuple(int(v) for v in cols[u])))
+        p += g[u]
+    return {k: sorted(v) for k, v in out.items()}
+
+
+def library_residual(A, m):
+    resid = {i: [] for i in range(m)}
+    for u in pyformat.walk(A.ecspmv_export_image()):
+        if u["kind"] == "lane":
+            keep = (u["values"] & 0x7FFF) != 0
+            resid[u["row"]].extend(int(c) for c in u["cols"][keep])
+    return resid
+
+
+def oracle_for_matrix(W, bounds, max_g):
+    pat = (W.view(np.uint16) & 0x7FFF) != 0
+    blocks, resid = {}, {}
+    for r0, r1 in zip(bounds[:-1], bounds[1:]):
+        rows = [set(np.nonzero(pat[i])[0].tolist()) for i in range(r0, r1)]
+        bs, rs = xo.hierarchical_block_extraction(rows, max_granularity=max_g, max_delta=15)
+        for g, units in bs.items():
+            blocks.setdefault(g, []).extend((tuple(r0 + m for m in mem), cols) for mem, cols in units)
+        for i, c in enumerate(rs):
+            resid[r0 + i] = c
+    return {k: sorted(v) for k, v in blocks.items()}, resid
+
+
+def test_encoder_matches_oracle_matching_over_all_rows():
+    W = gen.make_matrix(gen.scaled(gen.config(1), 4), 0)[:96]
+    A = E.ecspmv_build_dense(W, E.make_opts(delta_bits=4, flags=B.FLAG_GLOBAL_MATCHING))
+    want, want_res = oracle_for_matrix(W, [0, W.shape[0]], 8)
+    assert library_block_sets(A) == want
+    assert library_residual(A, W.shape[0]) == want_res
+    assert sum(len(v) for v in want.values()) > 20
+
+
+@pytest.mark.parametrize("cid,div", [(1, 16), (0, 1)])
+def test_encoder_matches_oracle_per_panel(cid, div):
+    cfg = gen.scaled(gen.config(cid), div) if div > 1 else gen.config(cid)
+    W = gen.make_matrix(cfg, 0)
+    m = W.shape[0]
+    A = E.ecspmv_build_dense(W, E.make_opts(delta_bits=4))
+    nnz = np.count_nonzero(W.view(np.uint16) & 0x7FFF, axis=1).tolist()
+    bounds = xo.nnz_balanced_panels(nnz, A.ecspmv_stats().num_panels)
+    want, want_res = oracle_for_matrix(W, bounds, 8)
+    assert library_block_sets(A) == want
+    assert library_residual(A, m) == want_res

@@ -46,7 +46,7 @@ def test_error_paths_without_gpu():
     assert lib.ecspmv_build_dense(u.ctypes.data, 0, 64, 64, None, ctypes.byref(out)) == B.ERR_INVALID
     assert lib.ecspmv_build_dense(u.ctypes.data, 8, 64, 32, None, ctypes.byref(out)) == B.ERR_INVALID      # ld < n
     assert lib.ecspmv_build_dense(u.ctypes.data, 1, 70000, 70000, None, ctypes.byref(out)) == B.ERR_UNSUPPORTED
-    for bad in (dict(delta_bits=4), dict(max_granularity=3), dict(threads_per_wg=100)):
+    for bad in (dict(delta_bits=6), dict(max_granularity=3), dict(threads_per_wg=100)):
         o = E.make_opts(**bad)
         st = lib.ecspmv_build_dense(u.ctypes.data, 8, 64, 64, ctypes.byref(o), ctypes.byref(out))
         assert st in (B.ERR_UNSUPPORTED, B.ERR_INVALID) and not out.value

@@ -1,0 +1,161 @@
+"""GPU parity of the EC-CSR-4 path (4-bit delta indices, paper Sections 6.2 and 8.2) against the FP64 CPU oracle,
+element by element, inside the same acceptance band as the 8-bit path:
+|y_i - y_ref_i| <= 2e-3 * S_i + 1e-6 with S_i = sum_j |W_ij x_j|."""
+import numpy as np
+import pytest
+
+from oracle import oracle as orc
+from workloads import generators as gen
+
+pytestmark = pytest.mark.gpu
+
+REL, ABS = 2e-3, 1e-6
+
+
+@pytest.fixture(scope="module")
+def E():
+    import torch
+    assert torch.cuda.is_available()
+    import paper_2507_12205_amd as pkg
+    from paper_2507_12205_amd import device
+    pkg.binding.lib()            # fails loudly if the HIP library is not built
+    pkg.device = device
+    return pkg
+
+
+def run(E, W, x, **opts):
+    import torch
+    A = E.ecspmv_build_dense(W, E.make_opts(delta_bits=4, **opts))
+    assert A.ecspmv_stats().delta_bits == 4
+    E.device.upload(A)
+    xd = torch.from_numpy(x.view(np.int16)).cuda().view(torch.float16)
+    yd = torch.full((W.shape[0],), float("nan"), dtype=torch.float16, device="cuda")
+    E.device.run(A, xd, yd)
+    torch.cuda.synchronize()
+    return A, yd.cpu().numpy()
+
+
+def check(E, W, x, label, **opts):
+    print(f"[case] delta4 {label} shape={W.shape}", flush=True)
+    A, y = run(E, W, x, **opts)
+    y_ref, S = orc.spmv_oracle(W, x)
+    assert not np.isnan(y.astype(np.float64)).any(), "a row of y was not written"
+    err = np.abs(y.astype(np.float64) - y_ref)
+    lim = REL * S + ABS
+    bad = np.nonzero(err > lim)[0]
+    assert bad.size == 0, f"{label}: {bad.size} rows out of band, first {bad[:5]}, err {err[bad[:5]]}, lim {lim[bad[:5]]}"
+    return A, y
+
+
+@pytest.mark.parametrize("cid,div", [(0, 1), (1, 4), (2, 4), (3, 4), (4, 4)])
+def test_configs_reduced(E, cid, div):
+    cfg = gen.scaled(gen.config(cid), div) if div > 1 else gen.config(cid)
+    for sid in range(len(cfg.shapes)):
+        if cid == 3 and sid in (1, 2, 3, 5):
+            continue
+        W, x = gen.make_case(cfg, sid)
+        check(E, W, x, f"cfg{cid}/{cfg.shapes[sid][0]}/div{div}")
+
+
+@pytest.mark.parametrize("maxg", [1, 2, 16])
+def test_granularity_caps(E, maxg):
+    W, x = gen.make_case(gen.scaled(gen.config(1), 4), 0)       # density 0.5: blocks exist with 4-bit deltas too
+    A, _ = check(E, W, x, f"maxg{maxg}", max_granularity=maxg)
+    st = A.ecspmv_stats()
+    if maxg > 1:
+        assert st.nnz_by_g[1] > 0
+    for t in range(1, 5):
+        if (1 << t) > maxg:
+            assert st.nnz_by_g[t] == 0
+
+
+def test_identical_rows_make_coarse_blocks(E):
+    rng = np.random.default_rng(21)
+    base = rng.random(2048) < 0.5
+    W = np.zeros((64, 2048), dtype=np.float16)
+    W[:, base] = (rng.standard_normal((64, int(base.sum()))) * 0.02).astype(np.float16)
+    x = gen.make_vector(2048, seed=22)
+    for maxg in (4, 8, 16):
+        A, _ = check(E, W, x, f"identical/maxg{maxg}", max_granularity=maxg, num_panels=2)
+        st = A.ecspmv_stats()
+        assert st.nnz_by_g[{4: 2, 8: 3, 16: 4}[maxg]] > 0
+
+
+@pytest.mark.parametrize("panels,threads", [(1, 64), (3, 256), (64, 512), (500, 128)])
+def test_launch_shapes(E, panels, threads):
+    W, x = gen.small_random(517, 1031, 0.35, seed=5)
+    check(E, W, x, f"P{panels}/T{threads}", num_panels=panels, threads_per_wg=threads)
+
+
+def test_edge_shapes(E):
+    rng = np.random.default_rng(3)
+    cases = {
+        "single_row": gen.small_random(1, 777, 0.5, 1),
+        "single_col": gen.small_random(333, 1, 0.7, 2),
+        "one_by_one": (np.array([[0.5]], dtype=np.float16), np.array([2.0], dtype=np.float16)),
+        "ragged_n": gen.small_random(70, 1003, 0.3, 3),
+        "dense": gen.small_random(64, 512, 1.1, 4),
+        "very_sparse_many_fillers": gen.small_random(128, 5000, 0.002, 5),
+        "all_zero": (np.zeros((50, 80), dtype=np.float16), gen.make_vector(80, seed=9)),
+    }
+    W = np.zeros((96, 4096), dtype=np.float16)        # rows with exactly one entry
+    W[np.arange(96), rng.integers(0, 4096, 96)] = 1.5
+    cases["one_entry_rows"] = (W, gen.make_vector(4096, seed=8))
+    W = np.zeros((2, 65535), dtype=np.float16)        # the widest x; a gap of 65534 columns = 4368 fillers
+    W[0, [0, 65534]] = [1.0, -2.0]
+    W[1, 40000] = 3.0
+    cases["widest_x_long_gap"] = (W, gen.make_vector(65535, seed=10))
+    for label, (W, x) in cases.items():
+        check(E, W, x, label)
+
+
+def test_unit_vectors_return_columns_bit_exactly(E):
+    import torch
+    W, _ = gen.make_case(gen.scaled(gen.config(3), 8), 0)
+    A = E.ecspmv_build_dense(W, E.make_opts(delta_bits=4))
+    E.device.upload(A)
+    m, n = W.shape
+    yd = torch.empty(m, dtype=torch.float16, device="cuda")
+    for j in (0, 1, n // 2, n - 1):
+        x = np.zeros(n, dtype=np.float16)
+        x[j] = 1.0
+        xd = torch.from_numpy(x.view(np.int16)).cuda().view(torch.float16)
+        E.device.run(A, xd, yd)
+        torch.cuda.synchronize()
+        col = W[:, j].copy()
+        col[col == 0] = 0
+        assert np.array_equal(yd.cpu().numpy().view(np.uint16), col.view(np.uint16)), f"column {j}"
+
+
+def test_unstructured_input_without_extraction(E):
+    """The i.i.d. mask at density 0.2 with extraction off: 3.6 % of the stored elements are fillers."""
+    W, x = gen.make_case(gen.scaled(gen.config(4), 8), 0)
+    _, y4 = check(E, W, x, "cfg4 g1", max_granularity=1)
+    y_ref, S = orc.spmv_oracle(W, x)
+    assert np.max(np.abs(y4.astype(np.float64) - y_ref) / (REL * S + ABS)) < 0.5
+
+
+def test_mixed_widths_in_one_batch_call(E):
+    """ecspmv_run_batch with 8- and 4-bit images interleaved: launches are split where the width changes and every
+    y equals the one a lone launch gives, bit for bit."""
+    import torch
+    mats, xs, lone = [], [], []
+    for i, bits in enumerate((8, 4, 4, 8, 4)):
+        W, x = gen.small_random(200 + 50 * i, 900 + 100 * i, 0.3, seed=30 + i)
+        A = E.ecspmv_build_dense(W, E.make_opts(delta_bits=bits))
+        E.device.upload(A)
+        xd = torch.from_numpy(x.view(np.int16)).cuda().view(torch.float16)
+        yd = torch.empty(W.shape[0], dtype=torch.float16, device="cuda")
+        E.device.run(A, xd, yd)
+        torch.cuda.synchronize()
+        mats.append(A)
+        xs.append(xd)
+        lone.append(yd.cpu().numpy())
+        y_ref, S = orc.spmv_oracle(W, x)
+        assert np.all(np.abs(lone[-1].astype(np.float64) - y_ref) <= REL * S + ABS)
+    ys = [torch.full((len(l),), float("nan"), dtype=torch.float16, device="cuda") for l in lone]
+    E.ecspmv_run_batch(mats, [x.data_ptr() for x in xs], [y.data_ptr() for y in ys],
+                       torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    for i, (y, l) in enumerate(zip(ys, lone)):
+        assert np.array_equal(y.cpu().numpy().view(np.uint16), l.view(np.uint16)), i
