@@ -41,6 +41,8 @@ def parse_args():
     ap.add_argument("--config", type=int, default=3, help="workload config id (workloads/generators.py)")
     ap.add_argument("--copies", type=int, default=0, help="seeded copies in the rotation set (0 = enough for the config's cold-cache size)")
     ap.add_argument("--max-granularity", type=int, default=0)
+    ap.add_argument("--delta-bits", type=int, default=0, choices=[0, 4, 8],
+                    help="width of the delta indices: 8 = EC-CSR-8 (default), 4 = EC-CSR-4")
     ap.add_argument("--panels", type=int, default=0)
     ap.add_argument("--threads-per-wg", type=int, default=0)
     ap.add_argument("--launch", choices=["single", "groups", "all"], default="single",
@@ -85,7 +87,7 @@ def main():
     cfg = gen.config(args.config)
     nshapes = len(cfg.shapes)
     opts = E.make_opts(max_granularity=args.max_granularity, num_panels=args.panels,
-                       threads_per_wg=args.threads_per_wg)
+                       threads_per_wg=args.threads_per_wg, delta_bits=args.delta_bits)
     torch.cuda.set_device(0)
     stream = torch.cuda.current_stream()
     sh = int(stream.cuda_stream)
@@ -212,7 +214,8 @@ def main():
     # separate profiler runs of this same command, so it is read from the committed summary, not sampled here
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "ecspmv_kernel_config3_hbm_traffic.json")
-    if args.config == 3 and not (args.max_granularity or args.panels or args.threads_per_wg) and os.path.exists(tpath):
+    default_build = not (args.max_granularity or args.panels or args.threads_per_wg or args.delta_bits in (4,))
+    if args.config == 3 and default_build and os.path.exists(tpath):
         with open(tpath) as f:
             traffic = json.load(f).get("traffic_bytes_per_launch")
 
@@ -225,7 +228,8 @@ def main():
                                + ", ".join(f"{nm} {m}x{n}" for nm, m, n in cfg.shapes)
                                + f"; density {cfg.density}; rotation of {copies} seeded copies, "
                                f"{image_total / 2**20:.0f} MiB of EC-CSR images (cold cache)",
-                   "spmv_per_step": nshapes, "rotation_copies": copies},
+                   "spmv_per_step": nshapes, "rotation_copies": copies,
+                   "format": f"EC-CSR-{mats[0][0]['st'].delta_bits}"},
         "us_per_spmv": round(us_per_spmv, 3),
         "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",

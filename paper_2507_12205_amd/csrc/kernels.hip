@@ -33,10 +33,19 @@ __device__ __forceinline__ float dpp_f(float old, float src)
 #define ECS_D2 2
 #define ECS_DR 1
 #endif
+#ifndef ECS_KATTR
+#define ECS_KATTR
+#endif
+#ifndef ECS_DR0B
+#define ECS_DR0B 2
+#endif
 // Register buffers per set (4-, 2- and 1-grained).  Measured on the box: one buffer for the 4-grained and residual
-// sets and two for the 2-grained set keep the kernel at 76 VGPRs, so three 512-thread workgroups share a compute
-// unit; deeper buffering costs that third workgroup and is slower.
-constexpr int D4 = ECS_D4, D2 = ECS_D2, DR = ECS_DR;
+// sets and two for the 2-grained set keep the kernel at 72 VGPRs, so three 512-thread workgroups share a compute
+// unit; deeper buffering costs that third workgroup and is slower.  An image with no blocks at all (only the
+// residual set) leaves room for two residual buffers at under 64 VGPRs: faster inside a batch, where many
+// wavefronts share a compute unit and each must keep more bytes on the way, slower for a lone launch, whose
+// wavefronts have one or two chunks each.
+constexpr int D4 = ECS_D4, D2 = ECS_D2, DR = ECS_DR, DR0B = ECS_DR0B;
 
 constexpr int DPP_ROW_SHR1 = 0x111, DPP_ROW_SHR2 = 0x112, DPP_ROW_SHR4 = 0x114, DPP_ROW_SHR8 = 0x118;
 constexpr int DPP_ROW_BCAST15 = 0x142, DPP_ROW_BCAST31 = 0x143;
@@ -371,9 +380,9 @@ struct ResidualSet {
 };
 
 // TM: bit t set = the image holds units of granularity 2 << t somewhere (the residual set is always handled);
-// DB: width of the delta indices in bits
-template <int TM, int DB>
-__global__ __launch_bounds__(1024) void ecspmv_kernel(const ecs::EcsBatch batch)
+// DB: width of the delta indices in bits; BATCH: buffer depths for a launch that carries several SpMVs
+template <int TM, int DB, bool BATCH>
+__global__ __launch_bounds__(1024) ECS_KATTR void ecspmv_kernel(const ecs::EcsBatch batch)
 {
     // which SpMV of the batch this workgroup works for (one item in the plain case)
     uint32_t k = 0, block0 = 0;
@@ -429,7 +438,7 @@ __global__ __launch_bounds__(1024) void ecspmv_kernel(const ecs::EcsBatch batch)
     BlockSet<8, DB, 1> b8;
     BlockSet<4, DB, wide ? 1 : D4> b4;
     BlockSet<2, DB, wide ? 2 : D2> b2;
-    ResidualSet<DB, wide ? 2 : DR> rs;
+    ResidualSet<DB, wide ? 2 : (TM == 0 && BATCH ? DR0B : DR)> rs;
     if constexpr ((TM & 8) != 0) b16.prologue(c, hdr, 3);
     if constexpr ((TM & 4) != 0) b8.prologue(c, hdr, 2);
     if constexpr ((TM & 2) != 0) b4.prologue(c, hdr, 1);
@@ -519,26 +528,30 @@ __global__ __launch_bounds__(1024) void stream_read_kernel(const uint4 *__restri
 
 namespace ecs {
 
-template <int TM, int DB>
+template <int TM, int DB, bool BATCH>
 static int launch_k(const EcsBatch &batch, uint32_t threads, uint32_t lds_bytes, void *stream)
 {
     static thread_local uint32_t attr_set_for = 0;
     if (lds_bytes > 65536 && lds_bytes > attr_set_for) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(ecspmv_kernel<TM, DB>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(ecspmv_kernel<TM, DB, BATCH>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
         if (e != hipSuccess) return (int)e;
         attr_set_for = lds_bytes;
     }
     const uint32_t grid = batch.item[batch.count - 1].block_end;
-    hipLaunchKernelGGL((ecspmv_kernel<TM, DB>), dim3(grid), dim3(threads), lds_bytes, (hipStream_t)stream, batch);
+    hipLaunchKernelGGL((ecspmv_kernel<TM, DB, BATCH>), dim3(grid), dim3(threads), lds_bytes, (hipStream_t)stream, batch);
     return (int)hipGetLastError();
 }
 
 template <int TM>
 static int launch_tm(const EcsBatch &batch, uint32_t threads, uint32_t lds_bytes, uint32_t delta_bits, void *stream)
 {
-    return delta_bits == 4 ? launch_k<TM, 4>(batch, threads, lds_bytes, stream)
-                           : launch_k<TM, 8>(batch, threads, lds_bytes, stream);
+    // only the residual-only kernel has a second set of buffer depths
+    if (TM == 0 && batch.count > 1)
+        return delta_bits == 4 ? launch_k<TM, 4, TM == 0>(batch, threads, lds_bytes, stream)
+                               : launch_k<TM, 8, TM == 0>(batch, threads, lds_bytes, stream);
+    return delta_bits == 4 ? launch_k<TM, 4, false>(batch, threads, lds_bytes, stream)
+                           : launch_k<TM, 8, false>(batch, threads, lds_bytes, stream);
 }
 
 int launch_ecspmv(const EcsBatch &batch, uint32_t threads, uint32_t lds_bytes, uint32_t type_mask, uint32_t delta_bits,
