@@ -380,8 +380,9 @@ struct ResidualSet {
 };
 
 // TM: bit t set = the image holds units of granularity 2 << t somewhere (the residual set is always handled);
-// DB: width of the delta indices in bits; BATCH: buffer depths for a launch that carries several SpMVs
-template <int TM, int DB, bool BATCH>
+// DB: width of the delta indices in bits; BATCH: buffer depths for a launch that carries several SpMVs;
+// K: 16-byte pieces of [tables | x] each thread brings to LDS before the generic loop takes the rest
+template <int TM, int DB, bool BATCH, int K>
 __global__ __launch_bounds__(1024) ECS_KATTR void ecspmv_kernel(const ecs::EcsBatch batch)
 {
     // which SpMV of the batch this workgroup works for (one item in the plain case)
@@ -413,25 +414,41 @@ __global__ __launch_bounds__(1024) ECS_KATTR void ecspmv_kernel(const ecs::EcsBa
     c.lane = tid & 63;
     c.nwaves = nt >> 6;
 
-    // Everything the workgroup needs first is requested at once, oldest first: the panel header (each wavefront
-    // reads it for itself: lane l holds word l), the panel's tables and x on their way to LDS.  All of these loads
-    // are unconditional (indices clamped), so none of them makes a later wait inexact.
-    const uint32_t hword = reinterpret_cast<const uint32_t *>(panel)[c.lane & 31u];
+    // Everything the workgroup needs first is requested at once: the panel header (wave-uniform: scalar loads), and
+    // the panel's tables and x on their way to LDS, as one list of 16-byte pieces [tables | x] with K pieces per
+    // thread.  These loads are unconditional (indices wrapped), so none of them makes a later wait inexact; K is a
+    // template parameter, the smallest that covers the list, because every wave-wide load costs issue time on the
+    // way to the first barrier whether its lanes are needed or not.
+    const uint32_t *__restrict__ hp = reinterpret_cast<const uint32_t *>(panel);
+    uint32_t hdr[ECS_PANEL_HEADER / 4];
+#pragma unroll
+    for (int w = 0; w < (int)(ECS_PANEL_HEADER / 4); ++w) hdr[w] = hp[w];
     const uint4 *p4 = reinterpret_cast<const uint4 *>(panel);
     const uint32_t nmeta = meta_stride / 16u;
-    const uint4 m0 = p4[min(tid, nmeta - 1u)], m1 = p4[min(tid + nt, nmeta - 1u)];
     const uint32_t nvec = n / 8u;
     const bool x_fast = (reinterpret_cast<uintptr_t>(x) & 15) == 0 && nvec > 0;
-    const uint4 *xsrc = x_fast ? reinterpret_cast<const uint4 *>(x) : p4;
-    const uint32_t xlast = x_fast ? nvec - 1u : 0u;
-    const uint4 x0 = xsrc[min(tid, xlast)], x1 = xsrc[min(tid + nt, xlast)];
-    const uint4 x2 = xsrc[min(tid + 2u * nt, xlast)], x3 = xsrc[min(tid + 3u * nt, xlast)];
+    const uint4 *xsrc = reinterpret_cast<const uint4 *>(x);
+    const uint32_t ntot = nmeta + (x_fast ? nvec : 0u);         // nmeta >= 1
+    // Threads beyond the end of the list bring a piece a second time (same bytes to the same place).  Which one
+    // was measured: in a lone launch all of them repeat the last piece (one cache line, few such threads); with
+    // several SpMVs in the launch there are many such threads (K follows the widest x) and they wrap around, so
+    // that the lanes of a wavefront write to different LDS addresses.
+    const bool wrap = batch.count > 1;
+    auto piece_index = [&](uint32_t k) -> uint32_t {
+        const uint32_t idx = tid + k * nt;
+        return idx < ntot ? idx : (wrap ? idx % ntot : ntot - 1u);
+    };
+    auto piece = [&](uint32_t k) -> const uint4 * {
+        const uint32_t idx = piece_index(k);
+        return idx < nmeta ? p4 + idx : xsrc + (idx - nmeta);
+    };
+    uint4 s0 = *piece(0), s1 = s0, s2 = s0, s3 = s0;
+    if constexpr (K > 1) s1 = *piece(1);
+    if constexpr (K > 2) s2 = *piece(2), s3 = *piece(3);
+    __builtin_amdgcn_sched_barrier(0);      // these loads do not wait for the header: keep them ahead of those that do
 
     // As soon as the header is here, the first two chunks of every set are requested, before anything is computed
     // and before the tables and x have even reached LDS.
-    uint32_t hdr[ECS_PANEL_HEADER / 4];
-#pragma unroll
-    for (int w = 0; w < (int)(ECS_PANEL_HEADER / 4); ++w) hdr[w] = (uint32_t)__builtin_amdgcn_readlane((int)hword, w);
     // buffers per set: deeper where chunks are small and frequent, shallower where registers run out
     constexpr bool wide = (TM & 12) != 0;
     BlockSet<16, DB, 1> b16;
@@ -447,19 +464,23 @@ __global__ __launch_bounds__(1024) ECS_KATTR void ecspmv_kernel(const ecs::EcsBa
 
     // tables and x into LDS
     uint4 *meta4 = reinterpret_cast<uint4 *>(meta);
-    if (tid < nmeta) meta4[tid] = m0;
-    if (tid + nt < nmeta) meta4[tid + nt] = m1;
-    for (uint32_t i = tid + 2u * nt; i < nmeta; i += nt) meta4[i] = p4[i];
-    if (x_fast) {
-        if (tid < nvec) lds4[tid] = x0;
-        if (tid + nt < nvec) lds4[tid + nt] = x1;
-        if (tid + 2u * nt < nvec) lds4[tid + 2u * nt] = x2;
-        if (tid + 3u * nt < nvec) lds4[tid + 3u * nt] = x3;
-        for (uint32_t i = tid + 4u * nt; i < nvec; i += nt) lds4[i] = xsrc[i];
-        for (uint32_t i = nvec * 8u + tid; i < n; i += nt) xs[i] = x[i];
-    } else {
-        for (uint32_t i = tid; i < n; i += nt) xs[i] = x[i];
+    // (no branches here either: with a store under a branch the compiler moves the load down to it and waits for
+    // it there)
+    auto place = [&](uint32_t k) -> uint4 * {
+        const uint32_t idx = piece_index(k);
+        return idx < nmeta ? meta4 + idx : lds4 + (idx - nmeta);
+    };
+    *place(0) = s0;
+    if constexpr (K > 1) *place(1) = s1;
+    if constexpr (K > 2) *place(2) = s2, *place(3) = s3;
+    for (uint32_t idx = tid + (uint32_t)K * nt; idx < ntot; idx += nt) {
+        if (idx < nmeta)
+            meta4[idx] = p4[idx];
+        else
+            lds4[idx - nmeta] = xsrc[idx - nmeta];
     }
+    // what 16-byte pieces do not cover: the last n % 8 entries of x, or all of x if it is not 16-byte aligned
+    for (uint32_t i = (x_fast ? nvec * 8u : 0u) + tid; i < n; i += nt) xs[i] = x[i];
     __syncthreads();
 
     if constexpr ((TM & 8) != 0) b16.run(c);
@@ -528,19 +549,36 @@ __global__ __launch_bounds__(1024) void stream_read_kernel(const uint4 *__restri
 
 namespace ecs {
 
-template <int TM, int DB, bool BATCH>
+template <int TM, int DB, bool BATCH, int K>
 static int launch_k(const EcsBatch &batch, uint32_t threads, uint32_t lds_bytes, void *stream)
 {
     static thread_local uint32_t attr_set_for = 0;
     if (lds_bytes > 65536 && lds_bytes > attr_set_for) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(ecspmv_kernel<TM, DB, BATCH>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(ecspmv_kernel<TM, DB, BATCH, K>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
         if (e != hipSuccess) return (int)e;
         attr_set_for = lds_bytes;
     }
     const uint32_t grid = batch.item[batch.count - 1].block_end;
-    hipLaunchKernelGGL((ecspmv_kernel<TM, DB, BATCH>), dim3(grid), dim3(threads), lds_bytes, (hipStream_t)stream, batch);
+    hipLaunchKernelGGL((ecspmv_kernel<TM, DB, BATCH, K>), dim3(grid), dim3(threads), lds_bytes, (hipStream_t)stream, batch);
     return (int)hipGetLastError();
+}
+
+template <int TM, int DB, bool BATCH>
+static int launch_b(const EcsBatch &batch, uint32_t threads, uint32_t lds_bytes, void *stream)
+{
+    // staging pieces per thread: the largest [tables | x] list of the batch over the workgroup size
+    uint32_t most = 1;
+    for (uint32_t i = 0; i < batch.count; ++i) {
+        const EcsBatchItem &it = batch.item[i];
+        const bool aligned = (reinterpret_cast<uintptr_t>(it.x) & 15) == 0;
+        const uint32_t pieces = it.meta_stride / 16u + (aligned ? it.n / 8u : 0u);
+        most = pieces > most ? pieces : most;
+    }
+    const uint32_t per_thread = (most + threads - 1) / threads;
+    if (per_thread <= 1) return launch_k<TM, DB, BATCH, 1>(batch, threads, lds_bytes, stream);
+    if (per_thread <= 2) return launch_k<TM, DB, BATCH, 2>(batch, threads, lds_bytes, stream);
+    return launch_k<TM, DB, BATCH, 4>(batch, threads, lds_bytes, stream);
 }
 
 template <int TM>
@@ -548,10 +586,10 @@ static int launch_tm(const EcsBatch &batch, uint32_t threads, uint32_t lds_bytes
 {
     // only the residual-only kernel has a second set of buffer depths
     if (TM == 0 && batch.count > 1)
-        return delta_bits == 4 ? launch_k<TM, 4, TM == 0>(batch, threads, lds_bytes, stream)
-                               : launch_k<TM, 8, TM == 0>(batch, threads, lds_bytes, stream);
-    return delta_bits == 4 ? launch_k<TM, 4, false>(batch, threads, lds_bytes, stream)
-                           : launch_k<TM, 8, false>(batch, threads, lds_bytes, stream);
+        return delta_bits == 4 ? launch_b<TM, 4, TM == 0>(batch, threads, lds_bytes, stream)
+                               : launch_b<TM, 8, TM == 0>(batch, threads, lds_bytes, stream);
+    return delta_bits == 4 ? launch_b<TM, 4, false>(batch, threads, lds_bytes, stream)
+                           : launch_b<TM, 8, false>(batch, threads, lds_bytes, stream);
 }
 
 int launch_ecspmv(const EcsBatch &batch, uint32_t threads, uint32_t lds_bytes, uint32_t type_mask, uint32_t delta_bits,
