@@ -14,7 +14,8 @@
 // 128-bit load of lane j (j = 0..15) sits at byte k*256 + j*16 of the unit (the permutation of Section
 // 6.3.2 for 16-byte vectors) and holds halfs [8k, 8k+8) of that lane's run values[(4j+c)*g + r].
 // The unit of the residual set is a "lane unit": 16 consecutive elements of one row (16 delta bytes, 16 FP16
-// values); 64 lane units form a chunk that one wavefront decodes with a prefix scan over lane totals.
+// values); 64 lane units form a chunk that one wavefront decodes with a prefix scan over lane totals.  Every lane
+// unit leaves one FP32 partial sum in LDS; a row's lane units are consecutive, so the row's sum is a range of them.
 //
 // Delta width (Section 6.2, EC-CSR-8 / EC-CSR-4 of Section 8.2): `delta_bits` of the image header is 8 or 4.
 // With 4 bits two deltas share a byte, the earlier one in the low nibble; a unit then has 32 delta bytes (2 per
@@ -25,7 +26,7 @@
 #include <stdint.h>
 
 #define ECS_MAGIC            0x52534345u /* "ECSR" */
-#define ECS_VERSION          1u
+#define ECS_VERSION          2u
 #define ECS_IMAGE_HEADER     256u        /* bytes before panel 0 */
 #define ECS_UNIT_COLS        64u         /* block columns per unit of a g >= 2 set */
 #define ECS_LANE_ELEMS       16u         /* residual elements per lane unit */
@@ -41,7 +42,8 @@
 enum {
     PH_ROW0 = 0,        /* first output row of the panel */
     PH_NROWS = 1,       /* rows owned */
-    PH_NSLOTS = 2,      /* FP32 partial-sum slots; a row's slots are consecutive */
+    PH_NSLOTS = 2,      /* FP32 partial-sum slots of the block sets, one per (unit, row); a row's slots are consecutive.
+                           The residual set adds one partial sum per lane unit, kept after these in LDS. */
     PH_NRLANES = 3,     /* residual lane units */
     PH_NRENTRIES = 4,   /* residual row segments (one per row and chunk it appears in) */
     PH_ROWSLOT_OFF = 5, /* byte offset in panel: uint16 first slot of each row, nrows + 1 entries */
@@ -54,7 +56,9 @@ enum {
     PH_BD_OFF = 18,     /* +t: byte offset in panel: 64 (8-bit) or 32 (4-bit) delta bytes per unit */
     PH_BV_OFF = 22,     /* +t: byte offset in panel: 128 * g value bytes per unit */
     PH_PANEL_BYTES = 26,
-    PH_META_BYTES = 27
+    PH_META_BYTES = 27,
+    PH_ROWLU_OFF = 28,  /* byte offset in panel: uint32 first residual lane unit of each row, nrows + 1 entries */
+    PH_ZERO_OFF = 29    /* byte offset in panel of 16 zero bytes (what idle lanes of the last residual chunk load) */
 };
 
 typedef struct EcsRChunk {
@@ -66,7 +70,7 @@ typedef struct EcsRChunk {
 typedef struct EcsREntry {
     int32_t  c;          /* column before the segment's first element minus the sum of the deltas of all
                             earlier lanes of the chunk: col(l, k) = c + exclusive_scan(l) + local_prefix(k) */
-    uint16_t slot;       /* where the segment's partial sum goes */
+    uint16_t reserved_;  /* 0 */
     uint16_t row_local;  /* row - PH_ROW0 (used by the host decoder only) */
 } EcsREntry;
 

@@ -316,7 +316,7 @@ inline uint16_t value_at(const Csr &A, int64_t row, int32_t col)
 
 struct PanelImage {
     std::vector<uint8_t> bytes;
-    uint32_t meta_bytes = 0, nslots = 0;
+    uint32_t meta_bytes = 0, nslots = 0, lds_slots = 0;
     int64_t value_bytes = 0, delta_bytes = 0, pad_elements = 0, gap_pads = 0;
     int64_t nnz_by_g[5] = {0, 0, 0, 0, 0};
     int64_t units_by_g[5] = {0, 0, 0, 0, 0};
@@ -431,7 +431,7 @@ void encode_panel(const Csr &A, int64_t row0, int nrows, PanelUnits &pu, bool re
                 ch.head_mask |= 1ull << l;
                 EcsREntry e;
                 e.c = (int32_t)(lu.before - scan);
-                e.slot = 0;
+                e.reserved_ = 0;
                 e.row_local = (uint16_t)lu.row;
                 rentries.push_back(e);
             }
@@ -439,15 +439,19 @@ void encode_panel(const Csr &A, int64_t row0, int nrows, PanelUnits &pu, bool re
         }
     }
 
-    // ---- slots: one per (unit, member row) and one per residual row segment; a row's slots are consecutive
+    // ---- slots: one per (unit, member row), a row's slots are consecutive; the residual set needs no table for
+    // its partial sums (one per lane unit, in stream order) beyond the first lane unit of every row
     std::vector<uint32_t> per_row(nrows, 0);
     for (int t = 0; t < ECS_NUM_BTYPES; ++t)
         for (auto &u : pu.units[t])
             for (int r : u.rows) ++per_row[r];
-    for (auto &e : rentries) ++per_row[e.row_local];
+    std::vector<uint32_t> rowlu(nrows + 1, 0);
+    for (const LaneUnit &lu : lanes) ++rowlu[lu.row + 1];
+    for (int r = 0; r < nrows; ++r) rowlu[r + 1] += rowlu[r];
     std::vector<uint32_t> rowslot(nrows + 1, 0);
     for (int r = 0; r < nrows; ++r) rowslot[r + 1] = rowslot[r] + per_row[r];
     img.nslots = rowslot[nrows];
+    img.lds_slots = img.nslots + ECS_CHUNK_LANES * nchunks;
     if (img.nslots > 65535u || nrows > 65535) {
         img.err = -2;
         return;
@@ -465,6 +469,8 @@ void encode_panel(const Csr &A, int64_t row0, int nrows, PanelUnits &pu, bool re
     hdr[PH_NRENTRIES] = (uint32_t)rentries.size();
     hdr[PH_ROWSLOT_OFF] = off;
     off = align_up(off + 2u * (uint32_t)(nrows + 1), 16);
+    hdr[PH_ROWLU_OFF] = off;
+    off = align_up(off + 4u * (uint32_t)(nrows + 1), 16);
     for (int t = ECS_NUM_BTYPES - 1; t >= 0; --t) {
         const uint32_t g = 2u << t;
         hdr[PH_NUNITS + t] = (uint32_t)pu.units[t].size();
@@ -475,6 +481,8 @@ void encode_panel(const Csr &A, int64_t row0, int nrows, PanelUnits &pu, bool re
     off += (uint32_t)sizeof(EcsRChunk) * nchunks;
     hdr[PH_RENTRY_OFF] = off;
     off = align_up(off + (uint32_t)sizeof(EcsREntry) * (uint32_t)rentries.size(), 16);
+    hdr[PH_ZERO_OFF] = off;
+    off += 16;
     img.meta_bytes = off;
     hdr[PH_META_BYTES] = off;
     for (int t = ECS_NUM_BTYPES - 1; t >= 0; --t) {
@@ -538,13 +546,13 @@ void encode_panel(const Csr &A, int64_t row0, int nrows, PanelUnits &pu, bool re
             }
         }
     }
-    for (auto &e : rentries) e.slot = (uint16_t)cursor[e.row_local]++;
     for (int r = 0; r < nrows; ++r)
         if (cursor[r] != rowslot[r + 1]) img.err = -100;
 
     std::memcpy(P, hdr, sizeof(hdr));
     uint16_t *rs = (uint16_t *)(P + hdr[PH_ROWSLOT_OFF]);
     for (int r = 0; r <= nrows; ++r) rs[r] = (uint16_t)rowslot[r];
+    std::memcpy(P + hdr[PH_ROWLU_OFF], rowlu.data(), 4u * (size_t)(nrows + 1));
     if (nchunks) std::memcpy(P + hdr[PH_RCHUNK_OFF], rchunks.data(), sizeof(EcsRChunk) * nchunks);
     if (!rentries.empty()) std::memcpy(P + hdr[PH_RENTRY_OFF], rentries.data(), sizeof(EcsREntry) * rentries.size());
 }
@@ -604,7 +612,7 @@ int build_image(const Csr &A, const BuildParams &bp, Image &out)
         if (im.err) return im.err;
         stride = std::max<uint32_t>(stride, (uint32_t)im.bytes.size());
         meta = std::max(meta, im.meta_bytes);
-        slots = std::max(slots, im.nslots);
+        slots = std::max(slots, im.lds_slots);
     }
     meta = align_up(meta, 16);
     // 4 KB of zeros after the last panel: loads that stand in for missing chunks may run past a short last panel
@@ -770,8 +778,10 @@ int walk_image(const Image &im, Triples *tri, BlockSets *bs)
             for (uint32_t l = 0; l < nl; ++l) {
                 const uint64_t below = rch[c].head_mask & ((l == 63) ? ~0ull : ((2ull << l) - 1));
                 const EcsREntry &e = ren[rch[c].entry0 + (uint32_t)__builtin_popcountll(below) - 1];
-                const int row = pv.row_of_slot(e.slot);
-                if (row != (int)e.row_local) return -102;
+                const int row = (int)e.row_local;
+                const uint32_t *rowlu = (const uint32_t *)(pv.P + pv.hdr[PH_ROWLU_OFF]);
+                const uint32_t L = c * ECS_CHUNK_LANES + l;
+                if (row >= (int)pv.nrows || L < rowlu[row] || L >= rowlu[row + 1]) return -102;
                 int64_t rel = 0;
                 for (uint32_t k = 0; k < ECS_LANE_ELEMS; ++k) {
                     rel += get_delta(d + ECS_LANE_DBYTES(bits) * l, k, bits);

@@ -70,26 +70,6 @@ __device__ __forceinline__ int wave64_incl_scan(int v)
     return v;
 }
 
-// inclusive segmented sum over the wavefront: `head` is 1 on the first lane of a segment
-template <int CTRL, int ROW_MASK>
-__device__ __forceinline__ void seg_step(float &v, int &head)
-{
-    const float tv = dpp_f<CTRL, ROW_MASK>(0.0f, v);
-    const int th = dpp_i<CTRL, ROW_MASK>(0, head);
-    v = head ? v : v + tv;
-    head |= th;
-}
-__device__ __forceinline__ float wave64_seg_incl_scan(float v, int head)
-{
-    seg_step<DPP_ROW_SHR1, 0xF>(v, head);
-    seg_step<DPP_ROW_SHR2, 0xF>(v, head);
-    seg_step<DPP_ROW_SHR4, 0xF>(v, head);
-    seg_step<DPP_ROW_SHR8, 0xF>(v, head);
-    seg_step<DPP_ROW_BCAST15, 0xA>(v, head);
-    seg_step<DPP_ROW_BCAST31, 0xC>(v, head);
-    return v;
-}
-
 // sum over the 16 lanes of a DPP row, result in every lane
 __device__ __forceinline__ float row16_allreduce(float a)
 {
@@ -271,14 +251,17 @@ struct ChunkRegs {
     uint4 v0, v1;       // 16 FP16 values
 };
 
+// Lanes beyond the end of the last chunk load 16 zero bytes the panel keeps for them (zero deltas, zero values), so
+// that the arithmetic needs no masking.  Unconditional, like load_unit.
 template <int DB>
-__device__ __forceinline__ void load_chunk(const Ctx &c, uint32_t rd_off, uint32_t rv_off, uint32_t ch, uint32_t nlanes,
-                                           ChunkRegs<DB> &r)
+__device__ __forceinline__ void load_chunk(const Ctx &c, uint32_t rd_off, uint32_t rv_off, uint32_t zero_off, uint32_t ch,
+                                           uint32_t nlanes, ChunkRegs<DB> &r)
 {
     const uint32_t nl = min(64u, nlanes - 64u * ch);
-    const uint32_t ll = min(c.lane, nl - 1u);           // lanes beyond the chunk's end re-read its last lane unit
-    const uint32_t od = rd_off + (128u * DB) * ch + (2u * DB) * ll;
-    const uint32_t ov = rv_off + 2048u * ch + 16u * ll;
+    const bool active = c.lane < nl;
+    const uint32_t od = active ? rd_off + (128u * DB) * ch + (2u * DB) * c.lane : zero_off;
+    const uint32_t ov = active ? rv_off + 2048u * ch + 16u * c.lane : zero_off;
+    const uint32_t ow = active ? ov + 16u * nl : zero_off;
     if constexpr (DB == 8) {
         const uint4 t = load16(c.panel + od);
         r.d[0] = t.x, r.d[1] = t.y, r.d[2] = t.z, r.d[3] = t.w;
@@ -287,25 +270,22 @@ __device__ __forceinline__ void load_chunk(const Ctx &c, uint32_t rd_off, uint32
         r.d[0] = t.x, r.d[1] = t.y;
     }
     r.v0 = load16(c.panel + ov);
-    r.v1 = load16(c.panel + (ov + 16u * nl));
+    r.v1 = load16(c.panel + ow);
 }
 
-template <int DB>
-__device__ __forceinline__ void compute_chunk(const Ctx &c, const EcsRChunk *rch, const EcsREntry *ren, uint32_t ch,
-                                              uint32_t nlanes, const ChunkRegs<DB> &r)
+// One partial sum per lane unit goes to LDS (`part`, indexed by the lane unit's position in the residual stream); a
+// row's lane units are consecutive, so the final pass adds a range of them.  No cross-lane reduction is needed here.
+template <int DB, bool FENCE>
+__device__ __forceinline__ void compute_chunk(const Ctx &c, const EcsRChunk *rch, const EcsREntry *ren, float *part,
+                                              uint32_t ch, const ChunkRegs<DB> &r)
 {
-    const uint32_t nl = min(64u, nlanes - 64u * ch);
-    const bool active = c.lane < nl;
     // lane-local inclusive prefix of the 16 deltas
     uint32_t rel[16];
     constexpr int PER = 32 / DB;                  // deltas per 32-bit word
-    uint32_t dw[DB / 2];
-#pragma unroll
-    for (int w = 0; w < DB / 2; ++w) dw[w] = active ? r.d[w] : 0u;
     uint32_t run = 0;
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
-        run += (dw[i / PER] >> (DB * (i % PER))) & ((1u << DB) - 1u);
+        run += (r.d[i / PER] >> (DB * (i % PER))) & ((1u << DB) - 1u);
         rel[i] = run;
     }
     // wave64 prefix scan of the lane totals; the segment's entry folds base column and earlier lanes
@@ -313,8 +293,7 @@ __device__ __forceinline__ void compute_chunk(const Ctx &c, const EcsRChunk *rch
     const uint64_t mask = rch[ch].head_mask;
     const uint64_t le = (c.lane == 63) ? ~0ull : ((2ull << c.lane) - 1ull);
     const int seg = __popcll(mask & le) - 1;
-    const EcsREntry e = ren[rch[ch].entry0 + seg];
-    const int start = e.c + incl - (int)run;
+    const int start = ren[rch[ch].entry0 + seg].c + incl - (int)run;
     float acc = 0.0f;
     const uint32_t vw[8] = {r.v0.x, r.v0.y, r.v0.z, r.v0.w, r.v1.x, r.v1.y, r.v1.z, r.v1.w};
 #pragma unroll
@@ -323,20 +302,19 @@ __device__ __forceinline__ void compute_chunk(const Ctx &c, const EcsRChunk *rch
         const uint32_t hb = (i & 1) ? (word >> 16) : (word & 0xFFFF);
         acc = fma_h(hb, half_bits_to_float(c.xs[start + (int)rel[i]]), acc);
     }
-    acc = active ? acc : 0.0f;
-    // segmented wavefront reduction: the last lane of every row segment holds its sum
-    const int head = (int)((mask >> c.lane) & 1ull);
-    const float seg_sum = wave64_seg_incl_scan(acc, head);
-    const bool is_end = active && (c.lane + 1 == nl || ((mask >> (c.lane + 1)) & 1ull));
-    if (is_end) c.slots[e.slot] = seg_sum;
+    part[64u * ch + c.lane] = acc;
+    // Nothing ties one chunk's arithmetic to the next: with two buffers the scheduler would interleave two chunks
+    // and need 20 more registers, which costs a workgroup per compute unit where workgroups share one.
+    if constexpr (FENCE) __builtin_amdgcn_sched_barrier(0);
 }
 
-template <int DB, int DEPTH>
+template <int DB, int DEPTH, bool FENCE>
 struct ResidualSet {
     ChunkRegs<DB> buf[DEPTH];
-    uint32_t nlanes, n, c0, rd_off, rv_off;
+    uint32_t nlanes, n, c0, rd_off, rv_off, zero_off;
     const EcsRChunk *rch;
     const EcsREntry *ren;
+    float *part;
 
     __device__ __forceinline__ uint32_t chunk_of(const Ctx &c, uint32_t i) const { return c0 + i * c.nwaves; }
     __device__ __forceinline__ void prologue(const Ctx &c, const uint32_t *hdr)
@@ -344,6 +322,8 @@ struct ResidualSet {
         nlanes = hdr[PH_NRLANES];
         rd_off = hdr[PH_RD_OFF];
         rv_off = hdr[PH_RV_OFF];
+        zero_off = hdr[PH_ZERO_OFF];
+        part = c.slots + hdr[PH_NSLOTS];
         rch = reinterpret_cast<const EcsRChunk *>(c.meta + hdr[PH_RCHUNK_OFF]);
         ren = reinterpret_cast<const EcsREntry *>(c.meta + hdr[PH_RENTRY_OFF]);
         const uint32_t nch = (nlanes + 63u) >> 6;
@@ -353,7 +333,8 @@ struct ResidualSet {
 #pragma unroll
         for (int d = 0; d < DEPTH; ++d) {
             const bool have = (uint32_t)d < n;
-            load_chunk<DB>(c, have ? rd_off : 0u, have ? rv_off : 0u, have ? chunk_of(c, d) : 0u, have ? nlanes : 1u, buf[d]);
+            load_chunk<DB>(c, have ? rd_off : 0u, have ? rv_off : 0u, have ? zero_off : 0u, have ? chunk_of(c, d) : 0u,
+                           have ? nlanes : 1u, buf[d]);
         }
     }
     __device__ __forceinline__ void run(const Ctx &c)
@@ -362,20 +343,20 @@ struct ResidualSet {
         for (; i + 2 * DEPTH - 1 < n; i += DEPTH) {
 #pragma unroll
             for (int d = 0; d < DEPTH; ++d) {
-                compute_chunk<DB>(c, rch, ren, chunk_of(c, i + d), nlanes, buf[d]);
-                load_chunk<DB>(c, rd_off, rv_off, chunk_of(c, i + DEPTH + d), nlanes, buf[d]);
+                compute_chunk<DB, FENCE>(c, rch, ren, part, chunk_of(c, i + d), buf[d]);
+                load_chunk<DB>(c, rd_off, rv_off, zero_off, chunk_of(c, i + DEPTH + d), nlanes, buf[d]);
             }
         }
 #pragma unroll
         for (int d = 0; d < DEPTH; ++d) {
             if (i + d < n) {
-                compute_chunk<DB>(c, rch, ren, chunk_of(c, i + d), nlanes, buf[d]);
-                if (i + DEPTH + d < n) load_chunk<DB>(c, rd_off, rv_off, chunk_of(c, i + DEPTH + d), nlanes, buf[d]);
+                compute_chunk<DB, FENCE>(c, rch, ren, part, chunk_of(c, i + d), buf[d]);
+                if (i + DEPTH + d < n) load_chunk<DB>(c, rd_off, rv_off, zero_off, chunk_of(c, i + DEPTH + d), nlanes, buf[d]);
             }
         }
 #pragma unroll
         for (int d = 0; d < DEPTH; ++d)
-            if (i + DEPTH + d < n) compute_chunk<DB>(c, rch, ren, chunk_of(c, i + DEPTH + d), nlanes, buf[d]);
+            if (i + DEPTH + d < n) compute_chunk<DB, FENCE>(c, rch, ren, part, chunk_of(c, i + DEPTH + d), buf[d]);
     }
 };
 
@@ -455,7 +436,7 @@ __global__ __launch_bounds__(1024) ECS_KATTR void ecspmv_kernel(const ecs::EcsBa
     BlockSet<8, DB, 1> b8;
     BlockSet<4, DB, wide ? 1 : D4> b4;
     BlockSet<2, DB, wide ? 2 : D2> b2;
-    ResidualSet<DB, wide ? 2 : (TM == 0 && BATCH ? DR0B : DR)> rs;
+    ResidualSet<DB, wide ? 2 : (TM == 0 && BATCH ? DR0B : DR), BATCH> rs;
     if constexpr ((TM & 8) != 0) b16.prologue(c, hdr, 3);
     if constexpr ((TM & 4) != 0) b8.prologue(c, hdr, 2);
     if constexpr ((TM & 2) != 0) b4.prologue(c, hdr, 1);
@@ -490,14 +471,21 @@ __global__ __launch_bounds__(1024) ECS_KATTR void ecspmv_kernel(const ecs::EcsBa
     rs.run(c);
     __syncthreads();
 
-    // every row: add its slots in a fixed order (16 lanes stride over them, then a fixed tree), store FP16
+    // every row: add its slots and the partial sums of its lane units in a fixed order (16 lanes stride over them,
+    // then a fixed tree), store FP16
     const uint32_t nrows = hdr[PH_NROWS], row0 = hdr[PH_ROW0];
     const uint16_t *rowslot = reinterpret_cast<const uint16_t *>(meta + hdr[PH_ROWSLOT_OFF]);
+    const uint32_t *rowlu = reinterpret_cast<const uint32_t *>(meta + hdr[PH_ROWLU_OFF]);
+    const float *part = slots + hdr[PH_NSLOTS];
     const uint32_t j = tid & 15;
     for (uint32_t r = tid >> 4; r < nrows; r += nt >> 4) {
-        const uint32_t s0 = rowslot[r], s1 = rowslot[r + 1];
         float sum = 0.0f;
-        for (uint32_t s = s0 + j; s < s1; s += 16) sum += slots[s];
+        if constexpr (TM != 0) {
+            const uint32_t s0 = rowslot[r], s1 = rowslot[r + 1];
+            for (uint32_t q = s0 + j; q < s1; q += 16) sum += slots[q];
+        }
+        const uint32_t l0 = rowlu[r], l1 = rowlu[r + 1];
+        for (uint32_t q = l0 + j; q < l1; q += 16) sum += part[q];
         sum = row16_allreduce(sum);
         if (j == 0) y[row0 + r] = __half_as_ushort(__float2half_rn(sum));
     }

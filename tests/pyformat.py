@@ -8,7 +8,7 @@ import numpy as np
 
 IMAGE_HEADER = 256
 PH = dict(ROW0=0, NROWS=1, NSLOTS=2, NRLANES=3, NRENTRIES=4, ROWSLOT_OFF=5, RCHUNK_OFF=6, RENTRY_OFF=7,
-          RD_OFF=8, RV_OFF=9, NUNITS=10, UTAB_OFF=14, BD_OFF=18, BV_OFF=22, PANEL_BYTES=26, META_BYTES=27)
+          RD_OFF=8, RV_OFF=9, NUNITS=10, UTAB_OFF=14, BD_OFF=18, BV_OFF=22, PANEL_BYTES=26, META_BYTES=27, ROWLU_OFF=28, ZERO_OFF=29)
 
 
 def image_header(img: np.ndarray) -> dict:
@@ -67,6 +67,11 @@ def walk(img: np.ndarray):
         nlanes = int(hdr[PH["NRLANES"]])
         rc, re_, rd, rv = (int(hdr[PH[k]]) for k in ("RCHUNK_OFF", "RENTRY_OFF", "RD_OFF", "RV_OFF"))
         prev_row = -1
+        o = int(hdr[PH["ROWLU_OFF"]])
+        rowlu = P[o:o + 4 * (nrows + 1)].view(np.uint32).astype(np.int64)
+        assert rowlu[0] == 0 and rowlu[-1] == nlanes and np.all(np.diff(rowlu) >= 0)
+        z = int(hdr[PH["ZERO_OFF"]])
+        assert not P[z:z + 16].any()
         for c in range((nlanes + 63) // 64):
             ch = P[rc + 16 * c: rc + 16 * (c + 1)]
             mask = int(ch[:8].view(np.uint64)[0])
@@ -77,15 +82,15 @@ def walk(img: np.ndarray):
                 seg = bin(mask & ((2 << l) - 1)).count("1") - 1
                 e = P[re_ + 8 * (entry0 + seg): re_ + 8 * (entry0 + seg + 1)]
                 cc = int(e[:4].view(np.int32)[0])
-                slot, row_local = (int(v) for v in e[4:8].view(np.uint16))
+                _, row_local = (int(v) for v in e[4:8].view(np.uint16))
                 d = deltas_of(P[rd + cdb * c + ldb * l: rd + cdb * c + ldb * (l + 1)], bits)
                 v0 = P[rv + 2048 * c + 16 * l: rv + 2048 * c + 16 * (l + 1)].view(np.uint16)
                 v1 = P[rv + 2048 * c + 16 * nl + 16 * l: rv + 2048 * c + 16 * nl + 16 * (l + 1)].view(np.uint16)
                 cols = cc + excl + np.cumsum(d)
                 excl += int(d.sum())
-                assert row_of_slot(slot) == row_local
+                assert rowlu[row_local] <= 64 * c + l < rowlu[row_local + 1]     # a row's lane units are consecutive
                 yield dict(kind="lane", panel=p, row=row0 + row_local, deltas=d, cols=cols,
-                           values=np.concatenate([v0, v1]), first_of_row=(row_local != prev_row), slot=slot,
+                           values=np.concatenate([v0, v1]), first_of_row=(row_local != prev_row),
                            head=bool((mask >> l) & 1))
                 prev_row = row_local
 

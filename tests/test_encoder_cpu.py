@@ -306,7 +306,7 @@ def test_byte_accounting():
     stored_elems = nnz + st.pad_elements
     assert st.value_bytes == 2 * stored_elems and st.delta_bytes == stored_elems
     assert st.pad_elements <= 15 * m + st.gap_pad_elements
-    assert 0.49 < st.image_bytes / st.csr32_bytes < 0.56                  # FP16 value + 8-bit delta: about half of CSR-32
+    assert 0.49 < st.image_bytes / st.csr32_bytes < 0.57                  # FP16 value + 8-bit delta: about half of CSR-32
     B2 = E.ecspmv_build_dense(W)                                          # with blocks: fewer index bytes
     s2 = B2.ecspmv_stats()
     assert s2.delta_bytes < st.delta_bytes and s2.x_access_cost < st.x_access_cost
