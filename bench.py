@@ -41,8 +41,9 @@ def parse_args():
     ap.add_argument("--config", type=int, default=3, help="workload config id (workloads/generators.py)")
     ap.add_argument("--copies", type=int, default=0, help="seeded copies in the rotation set (0 = enough for the config's cold-cache size)")
     ap.add_argument("--max-granularity", type=int, default=0)
-    ap.add_argument("--delta-bits", type=int, default=0, choices=[0, 4, 8],
-                    help="width of the delta indices: 8 = EC-CSR-8 (default), 4 = EC-CSR-4")
+    ap.add_argument("--delta-bits", type=int, default=4, choices=[4, 8],
+                    help="width of the delta indices: 4 = EC-CSR-4 (default: the smaller and faster format at the "
+                         "sparsities of the configs), 8 = EC-CSR-8; the other one is timed in the extras")
     ap.add_argument("--panels", type=int, default=0)
     ap.add_argument("--threads-per-wg", type=int, default=0)
     ap.add_argument("--launch", choices=["single", "groups", "all"], default="single",
@@ -214,7 +215,7 @@ def main():
     # separate profiler runs of this same command, so it is read from the committed summary, not sampled here
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "ecspmv_kernel_config3_hbm_traffic.json")
-    default_build = not (args.max_granularity or args.panels or args.threads_per_wg or args.delta_bits in (4,))
+    default_build = not (args.max_granularity or args.panels or args.threads_per_wg or args.delta_bits != 4)
     if args.config == 3 and default_build and os.path.exists(tpath):
         with open(tpath) as f:
             traffic = json.load(f).get("traffic_bytes_per_launch")
@@ -343,6 +344,56 @@ def main():
         out["csr_kernel"] = {"us_per_spmv": round(ms * 1e3 / (reps * nshapes), 3),
                              "gbps_of_csr32_bytes": round(csr_bytes * reps / (ms * 1e-3) / 1e9, 1),
                              "speedup_eccsr_over_csr": round((ms * 1e3 / (reps * nshapes)) / us_per_spmv, 3)}
+
+    if not args.no_extras:
+        # the other delta width on the same matrices: a rotation of up to three copies (> 512 MB of images)
+        other_bits = 8 if args.delta_bits == 4 else 4
+        oopts = E.make_opts(max_granularity=args.max_granularity, num_panels=args.panels,
+                            threads_per_wg=args.threads_per_wg, delta_bits=other_bits)
+        ncp = min(copies, 3)
+
+        def make_other(job):
+            copy, sid = job
+            W = keep_dense[sid][0] if copy == 0 else gen.make_matrix(cfg, sid, seed=0, copy=copy)
+            return copy, sid, E.ecspmv_build_dense(W, oopts)
+
+        olayers = [[None] * nshapes for _ in range(ncp)]
+        with ThreadPoolExecutor(max_workers=4) as ex:
+            for copy, sid, A in ex.map(make_other, [(c, s_) for c in range(ncp) for s_ in range(nshapes)]):
+                D.upload(A, stream=stream)
+                olayers[copy][sid] = dict(A=A, st=A.ecspmv_stats(), x=mats[copy][sid]["x"], y=mats[copy][sid]["y"])
+        obatch = [E.Batch([e["A"] for e in layer], [e["x"].data_ptr() for e in layer],
+                          [e["y"].data_ptr() for e in layer]) for layer in olayers]
+        obytes = [sum(algorithmic_bytes(e["st"]) for e in layer) for layer in olayers]
+        res = {}
+        for mode in ("single", "all"):
+            def go(layer_i):
+                if mode == "single":
+                    for e in olayers[layer_i]:
+                        e["A"].ecspmv_run(e["x"].data_ptr(), e["y"].data_ptr(), sh)
+                else:
+                    obatch[layer_i].ecspmv_run_batch(sh)
+            for w in range(ncp):
+                go(w)
+            torch.cuda.synchronize()
+            ev0.record(stream)
+            for s_ in range(args.steps):
+                go(s_ % ncp)
+            ev1.record(stream)
+            torch.cuda.synchronize()
+            ms = ev0.elapsed_time(ev1)
+            mv = sum(obytes[s_ % ncp] for s_ in range(args.steps))
+            res[mode] = {"us_per_step": round(ms * 1e3 / args.steps, 3), "gbps": round(mv / (ms * 1e-3) / 1e9, 1),
+                         "pct_of_hbm_peak": round(100.0 * mv / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 2)}
+        onnz = sum(e["st"].nnz for e in olayers[0])
+        oimg = sum(e["st"].image_bytes for e in olayers[0])
+        out["other_delta_width"] = {"format": f"EC-CSR-{other_bits}", "rotation_copies": ncp,
+                                    "bytes_per_nnz": round(oimg / onnz, 4),
+                                    "eccsr_over_csr32": round(oimg / sum(e["st"].csr32_bytes for e in olayers[0]), 4),
+                                    "nnz_by_granularity_1_2_4_8_16":
+                                        [int(sum(e["st"].nnz_by_g[k] for e in olayers[0])) for k in range(5)],
+                                    "by_launch_mode": res}
+        del olayers, obatch
 
     if args.calibrate_copy:
         src = torch.randint(0, 127, (256 << 20,), dtype=torch.int8, device="cuda")

@@ -60,6 +60,9 @@ typedef struct ecspmv_build_opts {
 #define ECSPMV_FLAG_GLOBAL_MATCHING  1ull /* one panel for extraction: row matching over all rows as in Algorithm 2
                                              (the launch then has a single workgroup: for studies on small inputs) */
 #define ECSPMV_FLAG_NO_REORDER       2ull /* keep blocks in extraction order instead of longest-first (Section 5) */
+#define ECSPMV_FLAG_KEEP_SMALL_SETS  4ull /* keep a coarsest block set even if it holds under 1 % of the stored entries.
+                                             Without the flag such a set is dropped (max_granularity is halved and the
+                                             matrix encoded again): every set costs the launch a pipeline stage. */
 
 /* What ecspmv_stats reports (Section 8.2 storage study, Table 2 padding). */
 typedef struct ecspmv_stats_t {

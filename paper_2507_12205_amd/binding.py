@@ -18,6 +18,7 @@ OK = 0
 ERR_INVALID, ERR_UNSUPPORTED, ERR_NOMEM, ERR_HIP, ERR_NOT_UPLOADED, ERR_TOO_SMALL = -1, -2, -3, -4, -5, -6
 FLAG_GLOBAL_MATCHING = 1
 FLAG_NO_REORDER = 2
+FLAG_KEEP_SMALL_SETS = 4
 
 EXPORTS = (
     "ecspmv_build_dense", "ecspmv_build_csr", "ecspmv_destroy", "ecspmv_stats", "ecspmv_decode",

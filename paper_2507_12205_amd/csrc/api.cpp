@@ -61,6 +61,7 @@ int parse_opts(const ecspmv_build_opts *o, ecs::BuildParams &bp)
     bp.threads_per_wg = t;
     bp.global_matching = (opts.flags & ECSPMV_FLAG_GLOBAL_MATCHING) != 0;
     bp.reorder = (opts.flags & ECSPMV_FLAG_NO_REORDER) == 0;
+    bp.keep_small_sets = (opts.flags & ECSPMV_FLAG_KEEP_SMALL_SETS) != 0;
     return ECSPMV_OK;
 }
 

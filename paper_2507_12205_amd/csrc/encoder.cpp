@@ -599,14 +599,29 @@ int build_image(const Csr &A, const BuildParams &bp, Image &out)
         }
         bound[P] = m;                                                        // the last panel ends at m
     }
-    std::vector<PanelImage> imgs(P);
+    std::vector<PanelImage> imgs;
     const int threads = resolve_threads(bp.num_threads);
-    parallel_for(P, threads, [&](int64_t p) {
-        const int64_t r0 = bound[p], r1 = (p + 1 == P) ? m : bound[p + 1];
-        PanelUnits pu;
-        extract_panel(A, r0, (int)(r1 - r0), bp.max_granularity, bp.max_rounds, bp.delta_bits, pu);
-        encode_panel(A, r0, (int)(r1 - r0), pu, bp.reorder, bp.delta_bits, imgs[p]);
-    });
+    // Every block set the image holds costs the SpMV launch a pipeline stage of its own, so a coarsest set that holds
+    // next to nothing (under 1 % of the stored entries over the whole matrix) is not worth having: the granularity
+    // cap is lowered and the matrix encoded again, until the coarsest set carries weight or no extraction is left.
+    for (int max_g = bp.max_granularity;; max_g >>= 1) {
+        imgs.assign(P, PanelImage());
+        parallel_for(P, threads, [&](int64_t p) {
+            const int64_t r0 = bound[p], r1 = (p + 1 == P) ? m : bound[p + 1];
+            PanelUnits pu;
+            extract_panel(A, r0, (int)(r1 - r0), max_g, bp.max_rounds, bp.delta_bits, pu);
+            encode_panel(A, r0, (int)(r1 - r0), pu, bp.reorder, bp.delta_bits, imgs[p]);
+        });
+        if (bp.keep_small_sets || max_g == 1) break;
+        int top = 0;                                                         // coarsest set present
+        int64_t by_t[ECS_NUM_BTYPES + 1] = {0, 0, 0, 0, 0};
+        for (auto &im : imgs)
+            for (int t = 1; t <= ECS_NUM_BTYPES; ++t) by_t[t] += im.nnz_by_g[t];
+        for (int t = 1; t <= ECS_NUM_BTYPES; ++t)
+            if (by_t[t] > 0) top = t;
+        if (top == 0 || by_t[top] * 100 >= nnz) break;
+        max_g = 1 << top;                                                    // halved by the loop: drops set `top`
+    }
     uint32_t stride = 256, meta = 16, slots = 1;
     for (auto &im : imgs) {
         if (im.err) return im.err;

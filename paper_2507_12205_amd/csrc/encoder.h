@@ -26,6 +26,7 @@ struct BuildParams {
     int threads_per_wg = 0;
     bool global_matching = false;
     bool reorder = true;
+    bool keep_small_sets = false;
 };
 
 struct Image {

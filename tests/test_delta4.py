@@ -188,7 +188,7 @@ def oracle_for_matrix(W, bounds, max_g):
 
 def test_encoder_matches_oracle_matching_over_all_rows():
     W = gen.make_matrix(gen.scaled(gen.config(1), 4), 0)[:96]
-    A = E.ecspmv_build_dense(W, E.make_opts(delta_bits=4, flags=B.FLAG_GLOBAL_MATCHING))
+    A = E.ecspmv_build_dense(W, E.make_opts(delta_bits=4, flags=B.FLAG_GLOBAL_MATCHING | B.FLAG_KEEP_SMALL_SETS))
     want, want_res = oracle_for_matrix(W, [0, W.shape[0]], 8)
     assert library_block_sets(A) == want
     assert library_residual(A, W.shape[0]) == want_res
@@ -200,9 +200,33 @@ def test_encoder_matches_oracle_per_panel(cid, div):
     cfg = gen.scaled(gen.config(cid), div) if div > 1 else gen.config(cid)
     W = gen.make_matrix(cfg, 0)
     m = W.shape[0]
-    A = E.ecspmv_build_dense(W, E.make_opts(delta_bits=4))
+    A = E.ecspmv_build_dense(W, E.make_opts(delta_bits=4, flags=B.FLAG_KEEP_SMALL_SETS))
     nnz = np.count_nonzero(W.view(np.uint16) & 0x7FFF, axis=1).tolist()
     bounds = xo.nnz_balanced_panels(nnz, A.ecspmv_stats().num_panels)
     want, want_res = oracle_for_matrix(W, bounds, 8)
     assert library_block_sets(A) == want
     assert library_residual(A, m) == want_res
+
+
+def test_a_coarsest_set_that_holds_next_to_nothing_is_dropped():
+    """Build rule of this library (not the paper's): a coarsest block set with under 1 % of the stored entries is not
+    kept, because every set costs the launch a pipeline stage; ECSPMV_FLAG_KEEP_SMALL_SETS keeps Algorithm 1's output."""
+    W = gen.make_matrix(gen.scaled(gen.config(3), 4), 0)            # at 4 bits only a few planted columns form units
+    kept = E.ecspmv_build_dense(W, E.make_opts(delta_bits=4, flags=B.FLAG_KEEP_SMALL_SETS)).ecspmv_stats()
+    auto = E.ecspmv_build_dense(W, E.make_opts(delta_bits=4))
+    st = auto.ecspmv_stats()
+    assert 0 < sum(kept.nnz_by_g[1:]) < 0.01 * kept.nnz
+    assert sum(st.nnz_by_g[1:]) == 0 and st.nnz_by_g[0] == st.nnz
+    assert roundtrip_ok(auto, W)
+    # a set that carries weight stays: 8-bit deltas on the same matrix
+    st8 = E.ecspmv_build_dense(W).ecspmv_stats()
+    assert st8.nnz_by_g[1] > 0.3 * st8.nnz
+    # only the coarsest set is judged, sets below it stay as they are
+    rng = np.random.default_rng(3)
+    V = np.zeros((64, 4096), dtype=np.float16)
+    V[:] = np.where(rng.random(V.shape) < 0.25, 1.0, 0.0)
+    V[:4, :] = 0
+    V[:4, np.sort(rng.choice(4096, 128, replace=False))] = 2.0        # four identical short rows: a little 4-grained
+    k = E.ecspmv_build_dense(V, E.make_opts(num_panels=1, flags=B.FLAG_KEEP_SMALL_SETS)).ecspmv_stats()
+    a = E.ecspmv_build_dense(V, E.make_opts(num_panels=1)).ecspmv_stats()
+    assert 0 < k.nnz_by_g[2] + k.nnz_by_g[3] < 0.01 * k.nnz and a.nnz_by_g[2] + a.nnz_by_g[3] == 0 and a.nnz_by_g[1] > 0

@@ -146,7 +146,7 @@ def test_encoder_matches_oracle_matching_over_all_rows(maxg):
     """One panel = the whole matrix: row matching over all rows, as the algorithm is printed."""
     cfg = gen.scaled(gen.config(3), 4)
     W = gen.make_matrix(cfg, 0)[:96]
-    A = E.ecspmv_build_dense(W, E.make_opts(max_granularity=maxg, flags=B.FLAG_GLOBAL_MATCHING))
+    A = E.ecspmv_build_dense(W, E.make_opts(max_granularity=maxg, flags=B.FLAG_GLOBAL_MATCHING | B.FLAG_KEEP_SMALL_SETS))
     want, want_res = oracle_for_matrix(W, [0, W.shape[0]], maxg)
     assert library_block_sets(A) == want
     assert library_residual(A, W.shape[0]) == want_res
@@ -158,7 +158,7 @@ def test_encoder_matches_oracle_per_panel(cid, div, panels):
     cfg = gen.scaled(gen.config(cid), div) if div > 1 else gen.config(cid)
     W = gen.make_matrix(cfg, 0)
     m = W.shape[0]
-    A = E.ecspmv_build_dense(W, E.make_opts(num_panels=panels))
+    A = E.ecspmv_build_dense(W, E.make_opts(num_panels=panels, flags=B.FLAG_KEEP_SMALL_SETS))
     P = A.ecspmv_stats().num_panels
     assert P == (panels or min(256, max(1, m // 16)))
     nnz = np.count_nonzero(W.view(np.uint16) & 0x7FFF, axis=1).tolist()
