@@ -22,7 +22,7 @@ FLAG_KEEP_SMALL_SETS = 4
 
 EXPORTS = (
     "ecspmv_build_dense", "ecspmv_build_csr", "ecspmv_destroy", "ecspmv_stats", "ecspmv_decode",
-    "ecspmv_block_sets", "ecspmv_device_bytes", "ecspmv_export_image", "ecspmv_upload", "ecspmv_run", "ecspmv_run_batch",
+    "ecspmv_block_sets", "ecspmv_device_bytes", "ecspmv_export_image", "ecspmv_upload", "ecspmv_run", "ecspmv_run_batch", "ecspmv_run_multi",
     "ecspmv_csr_build_dense", "ecspmv_csr_destroy", "ecspmv_csr_device_bytes", "ecspmv_csr_upload",
     "ecspmv_csr_run", "ecspmv_stream_read", "ecspmv_strerror", "ecspmv_last_hip_error",
 )
@@ -91,6 +91,7 @@ def lib() -> ctypes.CDLL:
     L.ecspmv_upload.argtypes = [c_void_p, c_void_p, c_size_t, c_void_p]
     L.ecspmv_run.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p]
     L.ecspmv_run_batch.argtypes = [c_void_p, c_void_p, c_void_p, c_int32, c_void_p]
+    L.ecspmv_run_multi.argtypes = [c_void_p, c_void_p, c_void_p, c_int32, c_void_p]
     L.ecspmv_csr_build_dense.argtypes = [c_void_p, c_int64, c_int64, c_int64, POINTER(c_void_p)]
     L.ecspmv_csr_destroy.argtypes = [c_void_p]
     L.ecspmv_csr_destroy.restype = None
@@ -194,6 +195,10 @@ class Matrix:
 
     def ecspmv_run(self, d_x: int, d_y: int, stream: int = 0) -> None:
         _check(lib().ecspmv_run(self._h, c_void_p(d_x), c_void_p(d_y), c_void_p(stream)), "ecspmv_run")
+
+    def ecspmv_run_multi(self, d_X: int, d_Y: int, nb: int, stream: int = 0) -> None:
+        _check(lib().ecspmv_run_multi(self._h, c_void_p(d_X), c_void_p(d_Y), c_int32(nb), c_void_p(stream)),
+               "ecspmv_run_multi")
 
 
 class Batch:

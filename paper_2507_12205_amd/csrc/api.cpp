@@ -270,6 +270,39 @@ int ecspmv_run(const ecspmv_matrix *A, const void *d_x, void *d_y, void *stream)
     return ecspmv_run_batch(&A, &d_x, &d_y, 1, stream);
 }
 
+int ecspmv_run_multi(const ecspmv_matrix *A, const void *d_X, void *d_Y, int32_t nb, void *stream)
+{
+    if (!A || !d_X || !d_Y) return ECSPMV_ERR_INVALID;
+    if (nb == 1) return ecspmv_run(A, d_X, d_Y, stream);
+    if (nb != 2 && nb != 4 && nb != 8) return ECSPMV_ERR_INVALID;
+    if ((reinterpret_cast<uintptr_t>(d_X) & 1) || (reinterpret_cast<uintptr_t>(d_Y) & 1)) return ECSPMV_ERR_INVALID;
+    if (!A->d_image) return ECSPMV_ERR_NOT_UPLOADED;
+    const ecs::Image &im = A->image;
+    if (im.type_mask & ~3u) return ECSPMV_ERR_UNSUPPORTED;            // 8- or 16-grained sets: registers run out
+    const uint32_t x_bytes = ((uint32_t)im.n * 2u * (uint32_t)nb + 15u) / 16u * 16u;
+    const uint32_t slot_bytes = (im.max_slots * 4u * (uint32_t)nb + 15u) / 16u * 16u;
+    const uint64_t lds = (uint64_t)x_bytes + im.meta_stride + slot_bytes;
+    int lim = 0;
+    int e = ecs::device_lds_limit(&lim);
+    if (e) return hip_status(e);
+    if (lds > (uint64_t)lim) return ECSPMV_ERR_UNSUPPORTED;           // x and the partial sums do not fit LDS
+    ecs::EcsBatch b;
+    std::memset(&b, 0, sizeof(b));
+    b.count = 1;
+    ecs::EcsBatchItem &it = b.item[0];
+    it.image = static_cast<const uint8_t *>(A->d_image);
+    it.x = static_cast<const uint16_t *>(d_X);
+    it.y = static_cast<uint16_t *>(d_Y);
+    it.n = (uint32_t)im.n;
+    it.panel_stride = im.panel_stride;
+    it.meta_stride = im.meta_stride;
+    it.x_bytes = x_bytes;
+    it.block_end = (uint32_t)im.num_panels;
+    const uint32_t threads = im.threads_per_wg ? (uint32_t)im.threads_per_wg : 1024u;
+    return hip_status(ecs::launch_ecspmv_multi(b, threads, (uint32_t)lds, im.type_mask, (uint32_t)im.delta_bits,
+                                               (uint32_t)nb, stream));
+}
+
 int ecspmv_csr_build_dense(const uint16_t *W, int64_t m, int64_t n, int64_t ld, ecspmv_csr **out)
 {
     if (!W || !out || m <= 0 || n <= 0 || ld < n) return ECSPMV_ERR_INVALID;

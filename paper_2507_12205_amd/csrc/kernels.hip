@@ -91,6 +91,28 @@ __device__ __forceinline__ float fma_h(uint32_t w_bits, float xf, float acc)
     return fmaf(half_bits_to_float(w_bits), xf, acc);
 }
 
+// the NB right-hand sides of one column sit side by side in LDS (x[col * NB + b]): one LDS read fetches them all
+template <int NB>
+__device__ __forceinline__ void gather_x(const uint16_t *xs, uint32_t col, float (&xv)[NB])
+{
+    if constexpr (NB == 1) {
+        xv[0] = half_bits_to_float(xs[col]);
+    } else if constexpr (NB == 2) {
+        const uint32_t w = *reinterpret_cast<const uint32_t *>(xs + 2u * col);
+        xv[0] = half_bits_to_float(w & 0xFFFF), xv[1] = half_bits_to_float(w >> 16);
+    } else if constexpr (NB == 4) {
+        const uint2 w = *reinterpret_cast<const uint2 *>(xs + 4u * col);
+        xv[0] = half_bits_to_float(w.x & 0xFFFF), xv[1] = half_bits_to_float(w.x >> 16);
+        xv[2] = half_bits_to_float(w.y & 0xFFFF), xv[3] = half_bits_to_float(w.y >> 16);
+    } else {
+        const uint4 w = *reinterpret_cast<const uint4 *>(xs + 8u * col);
+        xv[0] = half_bits_to_float(w.x & 0xFFFF), xv[1] = half_bits_to_float(w.x >> 16);
+        xv[2] = half_bits_to_float(w.y & 0xFFFF), xv[3] = half_bits_to_float(w.y >> 16);
+        xv[4] = half_bits_to_float(w.z & 0xFFFF), xv[5] = half_bits_to_float(w.z >> 16);
+        xv[6] = half_bits_to_float(w.w & 0xFFFF), xv[7] = half_bits_to_float(w.w >> 16);
+    }
+}
+
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 // 128-bit streaming load: every byte of the image is used once, so it is marked non-temporal
@@ -152,7 +174,7 @@ __device__ __forceinline__ void load_unit(const Ctx &c, uint32_t bd_off, uint32_
     for (int k = 0; k < G / 2; ++k) r.v[k] = load16(c.panel + (ov + 256u * k));
 }
 
-template <int G, int DB>
+template <int G, int DB, int NB>
 __device__ __forceinline__ void compute_unit(const Ctx &c, const uint16_t *utab, uint32_t u, uint32_t nu,
                                              const UnitRegs<G> &r)
 {
@@ -169,31 +191,37 @@ __device__ __forceinline__ void compute_unit(const Ctx &c, const uint16_t *utab,
     const int incl = row16_incl_scan((int)rel[3]);
     const uint16_t *ue = utab + uu * (1 + G);
     const uint32_t start = (uint32_t)ue[0] + (uint32_t)incl - rel[3];
-    float xv[4];
+    float xv[4][NB];
 #pragma unroll
-    for (int k = 0; k < 4; ++k) xv[k] = half_bits_to_float(c.xs[start + rel[k]]);
-    float acc[G];
+    for (int k = 0; k < 4; ++k) gather_x<NB>(c.xs, start + rel[k], xv[k]);
+    float acc[G][NB];
 #pragma unroll
-    for (int q = 0; q < G; ++q) acc[q] = 0.0f;
+    for (int q = 0; q < G; ++q)
+#pragma unroll
+        for (int b = 0; b < NB; ++b) acc[q][b] = 0.0f;
 #pragma unroll
     for (int f = 0; f < 4 * G; ++f) {                              // f = column * G + row
         const uint4 q = r.v[f >> 3];
         const uint32_t word = ((f >> 1) & 3) == 0 ? q.x : ((f >> 1) & 3) == 1 ? q.y : ((f >> 1) & 3) == 2 ? q.z : q.w;
         const uint32_t hb = (f & 1) ? (word >> 16) : (word & 0xFFFF);
-        acc[f % G] = fma_h(hb, xv[f / G], acc[f % G]);
+#pragma unroll
+        for (int b = 0; b < NB; ++b) acc[f % G][b] = fma_h(hb, xv[f / G][b], acc[f % G][b]);
     }
 #pragma unroll
-    for (int q = 0; q < G; ++q) acc[q] = row16_allreduce(acc[q]);
-    float out = acc[0];
+    for (int b = 0; b < NB; ++b) {
 #pragma unroll
-    for (int q = 1; q < G; ++q) out = (j == (uint32_t)q) ? acc[q] : out;
-    if (active && j < (uint32_t)G) c.slots[ue[1 + j]] = out;
+        for (int q = 0; q < G; ++q) acc[q][b] = row16_allreduce(acc[q][b]);
+        float out = acc[0][b];
+#pragma unroll
+        for (int q = 1; q < G; ++q) out = (j == (uint32_t)q) ? acc[q][b] : out;
+        if (active && j < (uint32_t)G) c.slots[(uint32_t)ue[1 + j] * NB + b] = out;
+    }
 }
 
 // A set's chunks c0, c0 + W, c0 + 2W, ... belong to this wavefront.  DEPTH register buffers take turns: all are
 // requested before anything is computed, and each is refilled right after it has been consumed, so a wavefront
 // always has its next DEPTH chunks on the way (the double buffering of Section 7, deeper and without copies).
-template <int G, int DB, int DEPTH>
+template <int G, int DB, int DEPTH, int NB>
 struct BlockSet {
     UnitRegs<G> buf[DEPTH];
     uint32_t nu, n, c0, bd_off, bv_off;
@@ -227,20 +255,20 @@ struct BlockSet {
         for (; i + 2 * DEPTH - 1 < n; i += DEPTH) {    // chunks i + DEPTH ... i + 2 DEPTH - 1 exist: unconditional refills
 #pragma unroll
             for (int d = 0; d < DEPTH; ++d) {
-                compute_unit<G, DB>(c, utab, unit_of(c, i + d), nu, buf[d]);
+                compute_unit<G, DB, NB>(c, utab, unit_of(c, i + d), nu, buf[d]);
                 load_unit<G, DB>(c, bd_off, bv_off, unit_of(c, i + DEPTH + d), nu, buf[d]);
             }
         }
 #pragma unroll
         for (int d = 0; d < DEPTH; ++d) {
             if (i + d < n) {
-                compute_unit<G, DB>(c, utab, unit_of(c, i + d), nu, buf[d]);
+                compute_unit<G, DB, NB>(c, utab, unit_of(c, i + d), nu, buf[d]);
                 if (i + DEPTH + d < n) load_unit<G, DB>(c, bd_off, bv_off, unit_of(c, i + DEPTH + d), nu, buf[d]);
             }
         }
 #pragma unroll
         for (int d = 0; d < DEPTH; ++d)
-            if (i + DEPTH + d < n) compute_unit<G, DB>(c, utab, unit_of(c, i + DEPTH + d), nu, buf[d]);
+            if (i + DEPTH + d < n) compute_unit<G, DB, NB>(c, utab, unit_of(c, i + DEPTH + d), nu, buf[d]);
     }
 };
 
@@ -275,7 +303,7 @@ __device__ __forceinline__ void load_chunk(const Ctx &c, uint32_t rd_off, uint32
 
 // One partial sum per lane unit goes to LDS (`part`, indexed by the lane unit's position in the residual stream); a
 // row's lane units are consecutive, so the final pass adds a range of them.  No cross-lane reduction is needed here.
-template <int DB, bool FENCE>
+template <int DB, bool FENCE, int NB>
 __device__ __forceinline__ void compute_chunk(const Ctx &c, const EcsRChunk *rch, const EcsREntry *ren, float *part,
                                               uint32_t ch, const ChunkRegs<DB> &r)
 {
@@ -294,21 +322,27 @@ __device__ __forceinline__ void compute_chunk(const Ctx &c, const EcsRChunk *rch
     const uint64_t le = (c.lane == 63) ? ~0ull : ((2ull << c.lane) - 1ull);
     const int seg = __popcll(mask & le) - 1;
     const int start = ren[rch[ch].entry0 + seg].c + incl - (int)run;
-    float acc = 0.0f;
+    float acc[NB];
+#pragma unroll
+    for (int b = 0; b < NB; ++b) acc[b] = 0.0f;
     const uint32_t vw[8] = {r.v0.x, r.v0.y, r.v0.z, r.v0.w, r.v1.x, r.v1.y, r.v1.z, r.v1.w};
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
         const uint32_t word = vw[i >> 1];
         const uint32_t hb = (i & 1) ? (word >> 16) : (word & 0xFFFF);
-        acc = fma_h(hb, half_bits_to_float(c.xs[start + (int)rel[i]]), acc);
+        float xv[NB];
+        gather_x<NB>(c.xs, (uint32_t)(start + (int)rel[i]), xv);
+#pragma unroll
+        for (int b = 0; b < NB; ++b) acc[b] = fma_h(hb, xv[b], acc[b]);
     }
-    part[64u * ch + c.lane] = acc;
+#pragma unroll
+    for (int b = 0; b < NB; ++b) part[(64u * ch + c.lane) * NB + b] = acc[b];
     // Nothing ties one chunk's arithmetic to the next: with two buffers the scheduler would interleave two chunks
     // and need 20 more registers, which costs a workgroup per compute unit where workgroups share one.
     if constexpr (FENCE) __builtin_amdgcn_sched_barrier(0);
 }
 
-template <int DB, int DEPTH, bool FENCE>
+template <int DB, int DEPTH, bool FENCE, int NB>
 struct ResidualSet {
     ChunkRegs<DB> buf[DEPTH];
     uint32_t nlanes, n, c0, rd_off, rv_off, zero_off;
@@ -323,7 +357,7 @@ struct ResidualSet {
         rd_off = hdr[PH_RD_OFF];
         rv_off = hdr[PH_RV_OFF];
         zero_off = hdr[PH_ZERO_OFF];
-        part = c.slots + hdr[PH_NSLOTS];
+        part = c.slots + hdr[PH_NSLOTS] * NB;
         rch = reinterpret_cast<const EcsRChunk *>(c.meta + hdr[PH_RCHUNK_OFF]);
         ren = reinterpret_cast<const EcsREntry *>(c.meta + hdr[PH_RENTRY_OFF]);
         const uint32_t nch = (nlanes + 63u) >> 6;
@@ -343,27 +377,28 @@ struct ResidualSet {
         for (; i + 2 * DEPTH - 1 < n; i += DEPTH) {
 #pragma unroll
             for (int d = 0; d < DEPTH; ++d) {
-                compute_chunk<DB, FENCE>(c, rch, ren, part, chunk_of(c, i + d), buf[d]);
+                compute_chunk<DB, FENCE, NB>(c, rch, ren, part, chunk_of(c, i + d), buf[d]);
                 load_chunk<DB>(c, rd_off, rv_off, zero_off, chunk_of(c, i + DEPTH + d), nlanes, buf[d]);
             }
         }
 #pragma unroll
         for (int d = 0; d < DEPTH; ++d) {
             if (i + d < n) {
-                compute_chunk<DB, FENCE>(c, rch, ren, part, chunk_of(c, i + d), buf[d]);
+                compute_chunk<DB, FENCE, NB>(c, rch, ren, part, chunk_of(c, i + d), buf[d]);
                 if (i + DEPTH + d < n) load_chunk<DB>(c, rd_off, rv_off, zero_off, chunk_of(c, i + DEPTH + d), nlanes, buf[d]);
             }
         }
 #pragma unroll
         for (int d = 0; d < DEPTH; ++d)
-            if (i + DEPTH + d < n) compute_chunk<DB, FENCE>(c, rch, ren, part, chunk_of(c, i + DEPTH + d), buf[d]);
+            if (i + DEPTH + d < n) compute_chunk<DB, FENCE, NB>(c, rch, ren, part, chunk_of(c, i + DEPTH + d), buf[d]);
     }
 };
 
 // TM: bit t set = the image holds units of granularity 2 << t somewhere (the residual set is always handled);
 // DB: width of the delta indices in bits; BATCH: buffer depths for a launch that carries several SpMVs;
-// K: 16-byte pieces of [tables | x] each thread brings to LDS before the generic loop takes the rest
-template <int TM, int DB, bool BATCH, int K>
+// K: 16-byte pieces of [tables | x] each thread brings to LDS before the generic loop takes the rest;
+// NB: right-hand sides handled at once (x holds n rows of NB values, y m rows of NB values)
+template <int TM, int DB, bool BATCH, int K, int NB>
 __global__ __launch_bounds__(1024) ECS_KATTR void ecspmv_kernel(const ecs::EcsBatch batch)
 {
     // which SpMV of the batch this workgroup works for (one item in the plain case)
@@ -375,7 +410,7 @@ __global__ __launch_bounds__(1024) ECS_KATTR void ecspmv_kernel(const ecs::EcsBa
     const ecs::EcsBatchItem &it = batch.item[k];
     const uint16_t *__restrict__ x = it.x;
     uint16_t *__restrict__ y = it.y;
-    const uint32_t n = it.n, meta_stride = it.meta_stride, x_bytes = it.x_bytes;
+    const uint32_t n = it.n * NB, meta_stride = it.meta_stride, x_bytes = it.x_bytes;   // n: FP16 entries of x
 
     extern __shared__ uint4 lds4[];
     uint8_t *lds = reinterpret_cast<uint8_t *>(lds4);
@@ -432,11 +467,11 @@ __global__ __launch_bounds__(1024) ECS_KATTR void ecspmv_kernel(const ecs::EcsBa
     // and before the tables and x have even reached LDS.
     // buffers per set: deeper where chunks are small and frequent, shallower where registers run out
     constexpr bool wide = (TM & 12) != 0;
-    BlockSet<16, DB, 1> b16;
-    BlockSet<8, DB, 1> b8;
-    BlockSet<4, DB, wide ? 1 : D4> b4;
-    BlockSet<2, DB, wide ? 2 : D2> b2;
-    ResidualSet<DB, wide ? 2 : (TM == 0 && BATCH ? DR0B : DR), BATCH> rs;
+    BlockSet<16, DB, 1, NB> b16;
+    BlockSet<8, DB, 1, NB> b8;
+    BlockSet<4, DB, wide ? 1 : D4, NB> b4;
+    BlockSet<2, DB, wide ? 2 : D2, NB> b2;
+    ResidualSet<DB, wide ? 2 : (TM == 0 && BATCH ? DR0B : DR), BATCH, NB> rs;
     if constexpr ((TM & 8) != 0) b16.prologue(c, hdr, 3);
     if constexpr ((TM & 4) != 0) b8.prologue(c, hdr, 2);
     if constexpr ((TM & 2) != 0) b4.prologue(c, hdr, 1);
@@ -476,18 +511,27 @@ __global__ __launch_bounds__(1024) ECS_KATTR void ecspmv_kernel(const ecs::EcsBa
     const uint32_t nrows = hdr[PH_NROWS], row0 = hdr[PH_ROW0];
     const uint16_t *rowslot = reinterpret_cast<const uint16_t *>(meta + hdr[PH_ROWSLOT_OFF]);
     const uint32_t *rowlu = reinterpret_cast<const uint32_t *>(meta + hdr[PH_ROWLU_OFF]);
-    const float *part = slots + hdr[PH_NSLOTS];
+    const float *part = slots + hdr[PH_NSLOTS] * NB;
     const uint32_t j = tid & 15;
     for (uint32_t r = tid >> 4; r < nrows; r += nt >> 4) {
-        float sum = 0.0f;
+        float sum[NB];
+#pragma unroll
+        for (int b = 0; b < NB; ++b) sum[b] = 0.0f;
         if constexpr (TM != 0) {
             const uint32_t s0 = rowslot[r], s1 = rowslot[r + 1];
-            for (uint32_t q = s0 + j; q < s1; q += 16) sum += slots[q];
+            for (uint32_t q = s0 + j; q < s1; q += 16)
+#pragma unroll
+                for (int b = 0; b < NB; ++b) sum[b] += slots[q * NB + b];
         }
         const uint32_t l0 = rowlu[r], l1 = rowlu[r + 1];
-        for (uint32_t q = l0 + j; q < l1; q += 16) sum += part[q];
-        sum = row16_allreduce(sum);
-        if (j == 0) y[row0 + r] = __half_as_ushort(__float2half_rn(sum));
+        for (uint32_t q = l0 + j; q < l1; q += 16)
+#pragma unroll
+            for (int b = 0; b < NB; ++b) sum[b] += part[q * NB + b];
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            const float t = row16_allreduce(sum[b]);
+            if (j == 0) y[(row0 + r) * NB + b] = __half_as_ushort(__float2half_rn(t));
+        }
     }
 }
 
@@ -537,18 +581,18 @@ __global__ __launch_bounds__(1024) void stream_read_kernel(const uint4 *__restri
 
 namespace ecs {
 
-template <int TM, int DB, bool BATCH, int K>
+template <int TM, int DB, bool BATCH, int K, int NB>
 static int launch_k(const EcsBatch &batch, uint32_t threads, uint32_t lds_bytes, void *stream)
 {
     static thread_local uint32_t attr_set_for = 0;
     if (lds_bytes > 65536 && lds_bytes > attr_set_for) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(ecspmv_kernel<TM, DB, BATCH, K>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(ecspmv_kernel<TM, DB, BATCH, K, NB>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
         if (e != hipSuccess) return (int)e;
         attr_set_for = lds_bytes;
     }
     const uint32_t grid = batch.item[batch.count - 1].block_end;
-    hipLaunchKernelGGL((ecspmv_kernel<TM, DB, BATCH, K>), dim3(grid), dim3(threads), lds_bytes, (hipStream_t)stream, batch);
+    hipLaunchKernelGGL((ecspmv_kernel<TM, DB, BATCH, K, NB>), dim3(grid), dim3(threads), lds_bytes, (hipStream_t)stream, batch);
     return (int)hipGetLastError();
 }
 
@@ -564,9 +608,9 @@ static int launch_b(const EcsBatch &batch, uint32_t threads, uint32_t lds_bytes,
         most = pieces > most ? pieces : most;
     }
     const uint32_t per_thread = (most + threads - 1) / threads;
-    if (per_thread <= 1) return launch_k<TM, DB, BATCH, 1>(batch, threads, lds_bytes, stream);
-    if (per_thread <= 2) return launch_k<TM, DB, BATCH, 2>(batch, threads, lds_bytes, stream);
-    return launch_k<TM, DB, BATCH, 4>(batch, threads, lds_bytes, stream);
+    if (per_thread <= 1) return launch_k<TM, DB, BATCH, 1, 1>(batch, threads, lds_bytes, stream);
+    if (per_thread <= 2) return launch_k<TM, DB, BATCH, 2, 1>(batch, threads, lds_bytes, stream);
+    return launch_k<TM, DB, BATCH, 4, 1>(batch, threads, lds_bytes, stream);
 }
 
 template <int TM>
@@ -578,6 +622,32 @@ static int launch_tm(const EcsBatch &batch, uint32_t threads, uint32_t lds_bytes
                                : launch_b<TM, 8, TM == 0>(batch, threads, lds_bytes, stream);
     return delta_bits == 4 ? launch_b<TM, 4, false>(batch, threads, lds_bytes, stream)
                            : launch_b<TM, 8, false>(batch, threads, lds_bytes, stream);
+}
+
+// several right-hand sides: one matrix per launch, the widest staging variant, images with 4-grained sets at most
+template <int TM, int DB>
+static int launch_nb(const EcsBatch &batch, uint32_t threads, uint32_t lds_bytes, uint32_t nb, void *stream)
+{
+    switch (nb) {
+    case 2: return launch_k<TM, DB, false, 4, 2>(batch, threads, lds_bytes, stream);
+    case 4: return launch_k<TM, DB, false, 4, 4>(batch, threads, lds_bytes, stream);
+    case 8: return launch_k<TM, DB, false, 4, 8>(batch, threads, lds_bytes, stream);
+    default: return (int)hipErrorInvalidValue;
+    }
+}
+
+int launch_ecspmv_multi(const EcsBatch &batch, uint32_t threads, uint32_t lds_bytes, uint32_t type_mask,
+                        uint32_t delta_bits, uint32_t nb, void *stream)
+{
+    const int top = (type_mask & 2) ? 3 : (type_mask & 1) ? 1 : 0;
+    if (delta_bits == 4) {
+        if (top == 3) return launch_nb<3, 4>(batch, threads, lds_bytes, nb, stream);
+        if (top == 1) return launch_nb<1, 4>(batch, threads, lds_bytes, nb, stream);
+        return launch_nb<0, 4>(batch, threads, lds_bytes, nb, stream);
+    }
+    if (top == 3) return launch_nb<3, 8>(batch, threads, lds_bytes, nb, stream);
+    if (top == 1) return launch_nb<1, 8>(batch, threads, lds_bytes, nb, stream);
+    return launch_nb<0, 8>(batch, threads, lds_bytes, nb, stream);
 }
 
 int launch_ecspmv(const EcsBatch &batch, uint32_t threads, uint32_t lds_bytes, uint32_t type_mask, uint32_t delta_bits,

@@ -57,6 +57,9 @@ def test_error_paths_without_gpu():
     assert lib.ecspmv_decode(A._h, ctypes.byref(n), buf.ctypes.data, buf.ctypes.data, v.ctypes.data) == B.ERR_TOO_SMALL
     assert lib.ecspmv_run(A._h, ctypes.c_void_p(16), ctypes.c_void_p(32), None) == B.ERR_NOT_UPLOADED
     assert lib.ecspmv_run(None, None, None, None) == B.ERR_INVALID
+    assert lib.ecspmv_run_multi(A._h, ctypes.c_void_p(16), ctypes.c_void_p(32), 4, None) == B.ERR_NOT_UPLOADED
+    assert lib.ecspmv_run_multi(A._h, ctypes.c_void_p(16), ctypes.c_void_p(32), 3, None) == B.ERR_INVALID
+    assert lib.ecspmv_run_multi(None, ctypes.c_void_p(16), ctypes.c_void_p(32), 2, None) == B.ERR_INVALID
     hs = (ctypes.c_void_p * 2)(A._h.value, A._h.value)
     ptrs = (ctypes.c_void_p * 2)(16, 32)
     assert lib.ecspmv_run_batch(hs, ptrs, ptrs, 2, None) == B.ERR_NOT_UPLOADED

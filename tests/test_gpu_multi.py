@@ -1,0 +1,129 @@
+"""GPU parity of ecspmv_run_multi (Y = W X for a few right-hand sides at once; the paper's problem statement with a
+small N, its Section 10 future work) against the FP64 CPU oracle, column by column, inside the acceptance band
+|y_i - y_ref_i| <= 2e-3 * S_i + 1e-6; and bit-equality of every column with the single-vector launch."""
+import numpy as np
+import pytest
+
+from oracle import oracle as orc
+from workloads import generators as gen
+
+pytestmark = pytest.mark.gpu
+
+REL, ABS = 2e-3, 1e-6
+
+
+@pytest.fixture(scope="module")
+def E():
+    import torch
+    assert torch.cuda.is_available()
+    import paper_2507_12205_amd as pkg
+    from paper_2507_12205_amd import device
+    pkg.binding.lib()
+    pkg.device = device
+    return pkg
+
+
+def make_X(n, nb, seed):
+    return np.stack([gen.make_vector(n, seed=seed + b) for b in range(nb)], axis=1).copy()      # (n, nb) row-major
+
+
+def check(E, W, nb, label, seed=100, **opts):
+    import torch
+    print(f"[case] multi {label} nb={nb} shape={W.shape}", flush=True)
+    m, n = W.shape
+    A = E.ecspmv_build_dense(W, E.make_opts(**opts))
+    E.device.upload(A)
+    X = make_X(n, nb, seed)
+    Xd = torch.from_numpy(X.view(np.int16)).cuda().view(torch.float16)
+    Yd = torch.full((m, nb), float("nan"), dtype=torch.float16, device="cuda")
+    E.device.run_multi(A, Xd, Yd)
+    torch.cuda.synchronize()
+    Y = Yd.cpu().numpy()
+    assert not np.isnan(Y.astype(np.float64)).any(), "an entry of Y was not written"
+    yd = torch.empty(m, dtype=torch.float16, device="cuda")
+    for b in range(nb):
+        xb = np.ascontiguousarray(X[:, b])
+        y_ref, S = orc.spmv_oracle(W, xb)
+        err = np.abs(Y[:, b].astype(np.float64) - y_ref)
+        bad = np.nonzero(err > REL * S + ABS)[0]
+        assert bad.size == 0, f"{label} column {b}: {bad.size} rows out of band, first {bad[:5]}"
+        # same chain of FP32 operations per column as the single-vector kernel: same bits
+        E.device.run(A, torch.from_numpy(xb.view(np.int16)).cuda().view(torch.float16), yd)
+        torch.cuda.synchronize()
+        assert np.array_equal(yd.cpu().numpy().view(np.uint16), np.ascontiguousarray(Y[:, b]).view(np.uint16)), (label, b)
+    return A
+
+
+@pytest.mark.parametrize("nb", [2, 4, 8])
+@pytest.mark.parametrize("bits", [4, 8])
+def test_configs_reduced(E, nb, bits):
+    for cid, div in ((0, 1), (1, 4), (3, 4), (4, 8)):
+        cfg = gen.scaled(gen.config(cid), div) if div > 1 else gen.config(cid)
+        W = gen.make_matrix(cfg, 0)
+        A = check(E, W, nb, f"cfg{cid}/div{div}/bits{bits}", delta_bits=bits, max_granularity=4)
+        if bits == 8 and cid in (1, 3):
+            st = A.ecspmv_stats()
+            assert st.nnz_by_g[1] > 0 and st.nnz_by_g[3] == 0          # block sets take part
+
+
+@pytest.mark.parametrize("nb", [2, 4, 8])
+def test_edge_shapes(E, nb):
+    rng = np.random.default_rng(7)
+    cases = {
+        "single_row": gen.small_random(1, 777, 0.5, 1)[0],
+        "single_col": gen.small_random(333, 1, 0.7, 2)[0],
+        "one_by_one": np.array([[0.5]], dtype=np.float16),
+        "ragged_n": gen.small_random(70, 1003, 0.3, 3)[0],
+        "all_zero": np.zeros((50, 80), dtype=np.float16),
+        "gaps_over_255": gen.small_random(128, 5000, 0.002, 5)[0],
+        "wide": gen.small_random(40, 6000, 0.1, 6)[0],
+    }
+    W = np.zeros((64, 2048), dtype=np.float16)                         # identical rows: 4-grained blocks
+    base = rng.random(2048) < 0.4
+    W[:, base] = (rng.standard_normal((64, int(base.sum()))) * 0.02).astype(np.float16)
+    cases["identical_rows"] = W
+    for label, W in cases.items():
+        check(E, W, nb, label, max_granularity=4)
+        check(E, W, nb, label + "/4bit", max_granularity=4, delta_bits=4)
+
+
+def test_launch_shapes(E):
+    W = gen.small_random(517, 1031, 0.35, seed=5)[0]
+    for panels, threads in ((1, 64), (3, 256), (64, 512), (500, 128)):
+        check(E, W, 4, f"P{panels}/T{threads}", num_panels=panels, threads_per_wg=threads, max_granularity=4)
+
+
+def test_full_size_projection(E):
+    """One 5120 x 5120 matrix of config 3 at full size, in the launch shape the bench times."""
+    W = gen.make_matrix(gen.config(3), 0)
+    check(E, W, 4, "cfg3 q full size", delta_bits=4)
+    check(E, W, 8, "cfg3 q full size 8-bit", delta_bits=8, max_granularity=4)
+
+
+def test_refusals(E):
+    import torch
+    B = E.binding
+    W = np.zeros((16, 3000), dtype=np.float16)
+    W[:, ::3] = 1.0                                                    # identical rows: an 8-grained set by default
+    A = E.ecspmv_build_dense(W)
+    assert A.ecspmv_stats().nnz_by_g[3] > 0
+    E.device.upload(A)
+    X = torch.zeros((3000, 2), dtype=torch.float16, device="cuda")
+    Y = torch.zeros((16, 2), dtype=torch.float16, device="cuda")
+    with pytest.raises(E.EcspmvError) as e:
+        A.ecspmv_run_multi(X.data_ptr(), Y.data_ptr(), 2)
+    assert e.value.status == B.ERR_UNSUPPORTED
+    for nb in (0, 3, 16):
+        with pytest.raises(E.EcspmvError) as e:
+            A.ecspmv_run_multi(X.data_ptr(), Y.data_ptr(), nb)
+        assert e.value.status == B.ERR_INVALID
+    wide = E.ecspmv_build_dense(gen.small_random(4, 60000, 0.01, 3)[0], E.make_opts(max_granularity=1))
+    E.device.upload(wide)
+    with pytest.raises(E.EcspmvError) as e:                            # 8 x 120 KB of x cannot sit in LDS
+        wide.ecspmv_run_multi(X.data_ptr(), Y.data_ptr(), 8)
+    assert e.value.status == B.ERR_UNSUPPORTED
+    fresh = E.ecspmv_build_dense(W, E.make_opts(max_granularity=2))
+    with pytest.raises(E.EcspmvError) as e:
+        fresh.ecspmv_run_multi(X.data_ptr(), Y.data_ptr(), 2)
+    assert e.value.status == B.ERR_NOT_UPLOADED
+    torch.cuda.synchronize()
