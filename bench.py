@@ -395,6 +395,58 @@ def main():
                                     "by_launch_mode": res}
         del olayers, obatch
 
+    if not args.no_extras:
+        # a few right-hand sides at once (ecspmv_run_multi): lone launches per shape class, cold rotation over up to
+        # three copies; images with 512 panels so that x (2*n*nb bytes) and the partial sums fit LDS more often
+        mopts = E.make_opts(max_granularity=min(args.max_granularity or 4, 4), num_panels=512,
+                            delta_bits=args.delta_bits)
+        ncp = min(copies, 3)
+
+        def make_multi(job):
+            copy, sid = job
+            W = keep_dense[sid][0] if copy == 0 else gen.make_matrix(cfg, sid, seed=0, copy=copy)
+            return copy, sid, E.ecspmv_build_dense(W, mopts)
+
+        mclasses = {}
+        with ThreadPoolExecutor(max_workers=4) as ex:
+            for copy, sid, A in ex.map(make_multi, [(c, s_) for c in range(ncp) for s_ in range(nshapes)]):
+                D.upload(A, stream=stream)
+                _, m_, n_ = cfg.shapes[sid]
+                mclasses.setdefault((m_, n_), []).append((A, A.ecspmv_stats()))
+        multi = {}
+        for (m_, n_), lst in mclasses.items():
+            row = {}
+            for nb in (1, 2, 4, 8):
+                X = (torch.randn((n_, nb), device="cuda") if nb > 1 else torch.randn((n_,), device="cuda")).half()
+                Y = torch.empty((m_, nb) if nb > 1 else (m_,), dtype=torch.float16, device="cuda")
+                try:
+                    for A, _ in lst:
+                        A.ecspmv_run_multi(X.data_ptr(), Y.data_ptr(), nb, sh)
+                except E.EcspmvError as err:
+                    if err.status != E.binding.ERR_UNSUPPORTED:
+                        raise
+                    row[f"nb{nb}"] = None                       # x and the partial sums do not fit LDS
+                    continue
+                torch.cuda.synchronize()
+                reps = max(2, (args.steps * nshapes) // (4 * len(lst)))
+                ev0.record(stream)
+                for _ in range(reps):
+                    for A, _ in lst:
+                        A.ecspmv_run_multi(X.data_ptr(), Y.data_ptr(), nb, sh)
+                ev1.record(stream)
+                torch.cuda.synchronize()
+                us = ev0.elapsed_time(ev1) * 1e3 / (reps * len(lst))
+                byt = sum(algorithmic_bytes(st) + (nb - 1) * 2 * (n_ + m_) for _, st in lst) / len(lst)
+                row[f"nb{nb}"] = {"us": round(us, 3), "gbps": round(byt / us / 1e3, 1),
+                                  "cold": bool(sum(int(st.image_bytes) for _, st in lst) > (300 << 20))}
+            base = row.get("nb1")
+            for nb in (2, 4, 8):
+                if base and row.get(f"nb{nb}"):
+                    row[f"nb{nb}"]["speedup_over_nb_single_launches"] = round(nb * base["us"] / row[f"nb{nb}"]["us"], 2)
+            multi[f"{m_}x{n_}"] = row
+        out["multi_rhs"] = {"format": f"EC-CSR-{mats[0][0]['st'].delta_bits}", "panels": 512, "per_shape": multi}
+        del mclasses
+
     if args.calibrate_copy:
         src = torch.randint(0, 127, (256 << 20,), dtype=torch.int8, device="cuda")
         dst = torch.empty_like(src)
