@@ -283,3 +283,47 @@ def test_too_wide_is_refused_on_the_host(E):
     with pytest.raises(E.EcspmvError) as ei:
         E.ecspmv_build_dense(W)
     assert ei.value.status == E.binding.ERR_UNSUPPORTED
+
+
+def test_launches_can_be_captured_in_a_graph(E):
+    """ecspmv_run, ecspmv_run_batch and ecspmv_run_multi allocate nothing and set no memory: a captured graph of them
+    gives the eager bits on every replay, with eager work and synchronisations between the replays."""
+    import torch
+    cfg = gen.scaled(gen.config(3), 4)
+    mats = []
+    for sid in (0, 4, 6):
+        W, x = gen.make_case(cfg, sid)
+        A = E.ecspmv_build_dense(W, E.make_opts(max_granularity=4))
+        E.device.upload(A)
+        xd = torch.from_numpy(x.view(np.int16)).cuda().view(torch.float16)
+        X4 = torch.stack([xd, -xd, xd * 0.5, xd * 2.0], dim=1).contiguous()
+        mats.append(dict(A=A, x=xd, X=X4, y=torch.empty(W.shape[0], dtype=torch.float16, device="cuda"),
+                         yb=torch.empty(W.shape[0], dtype=torch.float16, device="cuda"),
+                         Y=torch.empty((W.shape[0], 4), dtype=torch.float16, device="cuda")))
+
+    def work(sh):
+        for e in mats:
+            e["A"].ecspmv_run(e["x"].data_ptr(), e["y"].data_ptr(), sh)
+            e["A"].ecspmv_run_multi(e["X"].data_ptr(), e["Y"].data_ptr(), 4, sh)
+        E.ecspmv_run_batch([e["A"] for e in mats], [e["x"].data_ptr() for e in mats],
+                           [e["yb"].data_ptr() for e in mats], sh)
+
+    work(torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    want = [(e["y"].clone(), e["yb"].clone(), e["Y"].clone()) for e in mats]
+    side = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        work(torch.cuda.current_stream().cuda_stream)
+    for rep in range(3):
+        for e in mats:
+            e["y"].fill_(float("nan")), e["yb"].fill_(float("nan")), e["Y"].fill_(float("nan"))
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for e, (y, yb, Y) in zip(mats, want):
+            assert torch.equal(e["y"].view(torch.int16), y.view(torch.int16)), rep
+            assert torch.equal(e["yb"].view(torch.int16), yb.view(torch.int16)), rep
+            assert torch.equal(e["Y"].view(torch.int16), Y.view(torch.int16)), rep
+        work(torch.cuda.current_stream().cuda_stream)          # eager work between replays
+        torch.cuda.synchronize()
