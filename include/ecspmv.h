@@ -85,7 +85,7 @@ typedef struct ecspmv_stats_t {
     double   x_access_cost;            /* sum over stored entries of 1/g(e): the paper's x-access objective with L = 1 */
     double   build_seconds;
     int64_t  delta_hist[9];            /* residual deltas: 0, 1, 2-3, 4-7, ..., 64-127, 128-255 */
-    int32_t  delta_bits, reserved_;    /* delta width the image was built with */
+    int32_t  delta_bits, value_bits;   /* delta width the image was built with; 16 (FP16) or 32 (FP32) values */
 } ecspmv_stats_t;
 
 /* ---- offline phase (host) -------------------------------------------------------------------------- */
@@ -100,6 +100,14 @@ int ecspmv_build_dense(const uint16_t *W, int64_t m, int64_t n, int64_t ld,
 int ecspmv_build_csr(const int64_t *rowptr, const int32_t *col, const uint16_t *val,
                      int64_t m, int64_t n, const ecspmv_build_opts *opts, ecspmv_matrix **out);
 
+/* The same for FP32 values (the paper's other precision, Sections 3 and 8): W, and later x and y of ecspmv_run, are
+ * float.  An entry is stored iff it is neither +0 nor -0.  The image keeps 4-byte values; everything else (block
+ * extraction, delta indices, layout) is unchanged.  csr32_bytes / csr16_bytes of the stats then count 4-byte values. */
+int ecspmv_build_dense_f32(const float *W, int64_t m, int64_t n, int64_t ld,
+                           const ecspmv_build_opts *opts, ecspmv_matrix **out);
+int ecspmv_build_csr_f32(const int64_t *rowptr, const int32_t *col, const float *val,
+                         int64_t m, int64_t n, const ecspmv_build_opts *opts, ecspmv_matrix **out);
+
 void ecspmv_destroy(ecspmv_matrix *A);          /* NULL is a no-op */
 
 /* Fill *st (st->struct_size must be set by the caller). */
@@ -109,6 +117,8 @@ int ecspmv_stats(const ecspmv_matrix *A, ecspmv_stats_t *st);
  * Call with rows = cols = vals = NULL to get *nnz; then with host arrays of *nnz entries each (capacity
  * passed in *nnz).  Output order is image order (not sorted). */
 int ecspmv_decode(const ecspmv_matrix *A, int64_t *nnz, int32_t *rows, int32_t *cols, uint16_t *vals);
+/* The same for a matrix built with ecspmv_build_*_f32 (each of the two refuses the other kind: ECSPMV_ERR_INVALID). */
+int ecspmv_decode_f32(const ecspmv_matrix *A, int64_t *nnz, int32_t *rows, int32_t *cols, float *vals);
 
 /* The block sets (Algorithm 1's output): for every extracted unit, its granularity, its g original rows and
  * its 64 columns.  Call with NULLs to get the counts (*n_units, *n_rows = sum of g over units).
@@ -133,12 +143,13 @@ int ecspmv_upload(ecspmv_matrix *A, void *d_buf, size_t bytes, void *stream);
 
 /* y = W x (overwrites y; every one of the m entries is written).  d_x: device, n FP16, 2-byte aligned
  * (16-byte alignment takes the faster staging path).  d_y: device, m FP16.  x and y must not overlap.
+ * For a matrix built with ecspmv_build_*_f32, x and y are FP32 (4-byte aligned).
  * Asynchronous on `stream`: exactly one kernel launch, no allocation, no memset, no host synchronisation.
  * x must be finite: padding zeros are multiplied with x entries. */
 int ecspmv_run(const ecspmv_matrix *A, const void *d_x, void *d_y, void *stream);
 
 /* The same for `count` independent SpMVs in one kernel launch per 16 matrices (a launch also ends where the
- * delta width changes from one matrix to the next): y_i = W_i x_i.  As, d_xs, d_ys:
+ * delta width or the value width changes from one matrix to the next): y_i = W_i x_i.  As, d_xs, d_ys:
  * host arrays of `count` handles / device pointers.  The SpMVs must not depend on one another (no y_i may be an
  * x_j of the same call).  Meant for the
  * projections of a decoder layer that share a launch: workgroups of the next matrix start while the last ones of
@@ -151,7 +162,7 @@ int ecspmv_run_batch(const ecspmv_matrix *const *As, const void *const *d_xs, vo
  * FP16 (row-major: the nb values that belong to one column of W are adjacent), d_Y: device, m rows of nb FP16; every
  * entry of Y is written.  The deltas are decoded once and every stored entry of W is read once for all nb products.
  * One kernel launch, asynchronous on `stream`, no allocation.  nb = 1 is ecspmv_run.
- * ECSPMV_ERR_UNSUPPORTED if the image holds 8- or 16-grained block sets (build with max_granularity <= 4 for this
+ * ECSPMV_ERR_UNSUPPORTED for FP32 matrices, if the image holds 8- or 16-grained block sets (build with max_granularity <= 4 for this
  * call) or if 2*n*nb bytes of X plus 4*nb bytes per partial sum do not fit the LDS of a compute unit;
  * ECSPMV_ERR_INVALID for other nb. */
 int ecspmv_run_multi(const ecspmv_matrix *A, const void *d_X, void *d_Y, int32_t nb, void *stream);

@@ -45,6 +45,9 @@ def _load():
         lib.oracle_spmv_f64.restype = ctypes.c_int
         lib.oracle_spmv_f64.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
                                         ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+        lib.oracle_spmv_f64_from_f32.restype = ctypes.c_int
+        lib.oracle_spmv_f64_from_f32.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
+                                                 ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
         lib.oracle_half_to_double.restype = ctypes.c_double
         lib.oracle_half_to_double.argtypes = [ctypes.c_uint16]
         _lib = lib
@@ -77,6 +80,28 @@ def spmv_oracle_threads(W: np.ndarray, x: np.ndarray):
     if t < 0:
         raise MemoryError("oracle_spmv_f64")
     return y, S, int(t)
+
+
+def spmv_oracle_f32(W: np.ndarray, x: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
+    """(y_ref, S), both float64 of length m, from dense FP32 W (m, n) and FP32 x (n,): the FP32 precision of the paper."""
+    assert W.dtype == np.float32 and x.dtype == np.float32 and W.ndim == 2 and x.ndim == 1
+    m, n = W.shape
+    assert x.shape[0] == n
+    Wc = np.ascontiguousarray(W)
+    xc = np.ascontiguousarray(x)
+    y = np.zeros(m, dtype=np.float64)
+    S = np.zeros(m, dtype=np.float64)
+    if m:
+        _load().oracle_spmv_f64_from_f32(Wc.ctypes.data, m, n, n, xc.ctypes.data, y.ctypes.data, S.ctypes.data)
+    return y, S
+
+
+def pattern_triples_f32(W: np.ndarray):
+    """(rows, cols, FP32 bit patterns) of the stored entries of an FP32 W (neither +0 nor -0), sorted by (row, col)."""
+    assert W.dtype == np.float32
+    bits = np.ascontiguousarray(W).view(np.uint32)
+    rows, cols = np.nonzero((bits & 0x7FFFFFFF) != 0)
+    return rows.astype(np.int32), cols.astype(np.int32), bits[rows, cols].copy()
 
 
 def spmv_oracle_py(W: np.ndarray, x: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:

@@ -81,3 +81,31 @@ int oracle_spmv_f64(const uint16_t *W, int64_t m, int64_t n, int64_t ld,
     free(xd);
     return threads;
 }
+
+/*
+ * The same definition for the paper's FP32 precision (Section 3 states the problem for both; Section 8 measures
+ * both): W (m x n, leading dimension ld) and x are binary32; each input is converted exactly to FP64 (a C cast of a
+ * float to double is exact), products and sums are FP64, columns in natural order.  y, S: m doubles each.
+ * Returns the number of threads used.
+ */
+int oracle_spmv_f64_from_f32(const float *W, int64_t m, int64_t n, int64_t ld,
+                             const float *x, double *y, double *S)
+{
+    int threads = 1;
+#ifdef _OPENMP
+    threads = omp_get_max_threads();
+#pragma omp parallel for schedule(static)
+#endif
+    for (int64_t i = 0; i < m; ++i) {
+        const float *row = W + i * ld;
+        double acc = 0.0, mag = 0.0;
+        for (int64_t j = 0; j < n; ++j) {
+            double p = (double)row[j] * (double)x[j];
+            acc += p;
+            mag += fabs(p);
+        }
+        y[i] = acc;
+        if (S) S[i] = mag;
+    }
+    return threads;
+}

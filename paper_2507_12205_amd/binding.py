@@ -21,7 +21,8 @@ FLAG_NO_REORDER = 2
 FLAG_KEEP_SMALL_SETS = 4
 
 EXPORTS = (
-    "ecspmv_build_dense", "ecspmv_build_csr", "ecspmv_destroy", "ecspmv_stats", "ecspmv_decode",
+    "ecspmv_build_dense", "ecspmv_build_csr", "ecspmv_build_dense_f32", "ecspmv_build_csr_f32", "ecspmv_destroy",
+    "ecspmv_stats", "ecspmv_decode", "ecspmv_decode_f32",
     "ecspmv_block_sets", "ecspmv_device_bytes", "ecspmv_export_image", "ecspmv_upload", "ecspmv_run", "ecspmv_run_batch", "ecspmv_run_multi",
     "ecspmv_csr_build_dense", "ecspmv_csr_destroy", "ecspmv_csr_device_bytes", "ecspmv_csr_upload",
     "ecspmv_csr_run", "ecspmv_stream_read", "ecspmv_strerror", "ecspmv_last_hip_error",
@@ -43,7 +44,7 @@ class Stats(Structure):
                 ("threads_per_wg", c_int32), ("panel_stride", c_int64), ("meta_stride", c_int64),
                 ("lds_bytes", c_int64), ("max_panel_bytes", c_int64), ("min_panel_bytes", c_int64),
                 ("x_access_cost", c_double), ("build_seconds", c_double), ("delta_hist", c_int64 * 9),
-                ("delta_bits", c_int32), ("reserved_", c_int32)]
+                ("delta_bits", c_int32), ("value_bits", c_int32)]
 
     def as_dict(self) -> dict:
         out = {}
@@ -81,6 +82,9 @@ def lib() -> ctypes.CDLL:
     L = ctypes.CDLL(path)
     L.ecspmv_build_dense.argtypes = [c_void_p, c_int64, c_int64, c_int64, POINTER(BuildOpts), POINTER(c_void_p)]
     L.ecspmv_build_csr.argtypes = [c_void_p, c_void_p, c_void_p, c_int64, c_int64, POINTER(BuildOpts), POINTER(c_void_p)]
+    L.ecspmv_build_dense_f32.argtypes = [c_void_p, c_int64, c_int64, c_int64, POINTER(BuildOpts), POINTER(c_void_p)]
+    L.ecspmv_build_csr_f32.argtypes = [c_void_p, c_void_p, c_void_p, c_int64, c_int64, POINTER(BuildOpts), POINTER(c_void_p)]
+    L.ecspmv_decode_f32.argtypes = [c_void_p, POINTER(c_int64), c_void_p, c_void_p, c_void_p]
     L.ecspmv_destroy.argtypes = [c_void_p]
     L.ecspmv_destroy.restype = None
     L.ecspmv_stats.argtypes = [c_void_p, POINTER(Stats)]
@@ -167,6 +171,16 @@ class Matrix:
                "ecspmv_decode")
         return rows, cols, vals
 
+    def ecspmv_decode_f32(self):
+        n = c_int64(0)
+        _check(lib().ecspmv_decode_f32(self._h, byref(n), None, None, None), "ecspmv_decode_f32")
+        rows = np.empty(n.value, dtype=np.int32)
+        cols = np.empty(n.value, dtype=np.int32)
+        vals = np.empty(n.value, dtype=np.uint32)            # FP32 bit patterns
+        _check(lib().ecspmv_decode_f32(self._h, byref(n), rows.ctypes.data, cols.ctypes.data, vals.ctypes.data),
+               "ecspmv_decode_f32")
+        return rows, cols, vals
+
     def ecspmv_block_sets(self):
         nu, nr = c_int64(0), c_int64(0)
         _check(lib().ecspmv_block_sets(self._h, byref(nu), byref(nr), None, None, None), "ecspmv_block_sets")
@@ -227,6 +241,29 @@ def ecspmv_build_dense(W: np.ndarray, opts: BuildOpts | None = None) -> Matrix:
     out = c_void_p(0)
     _check(lib().ecspmv_build_dense(Wu.ctypes.data, m, n, Wu.strides[0] // 2, byref(opts) if opts else None,
                                     byref(out)), "ecspmv_build_dense")
+    return Matrix(out.value)
+
+
+def ecspmv_build_dense_f32(W: np.ndarray, opts: BuildOpts | None = None) -> Matrix:
+    if W.dtype != np.float32 or W.ndim != 2:
+        raise TypeError("W must be a 2-D float32 array")
+    if W.strides[1] != 4 or W.strides[0] % 4 or W.strides[0] < 4 * W.shape[1]:
+        W = np.ascontiguousarray(W)
+    m, n = W.shape
+    out = c_void_p(0)
+    _check(lib().ecspmv_build_dense_f32(W.ctypes.data, m, n, W.strides[0] // 4, byref(opts) if opts else None,
+                                        byref(out)), "ecspmv_build_dense_f32")
+    return Matrix(out.value)
+
+
+def ecspmv_build_csr_f32(rowptr: np.ndarray, col: np.ndarray, val: np.ndarray, m: int, n: int,
+                         opts: BuildOpts | None = None) -> Matrix:
+    rowptr = np.ascontiguousarray(rowptr, dtype=np.int64)
+    col = np.ascontiguousarray(col, dtype=np.int32)
+    val = np.ascontiguousarray(val, dtype=np.float32)
+    out = c_void_p(0)
+    _check(lib().ecspmv_build_csr_f32(rowptr.ctypes.data, col.ctypes.data, val.ctypes.data, m, n,
+                                      byref(opts) if opts else None, byref(out)), "ecspmv_build_csr_f32")
     return Matrix(out.value)
 
 

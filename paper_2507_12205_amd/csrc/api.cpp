@@ -84,6 +84,38 @@ int finish_build(const ecs::Csr &A, const ecs::BuildParams &bp, ecspmv_matrix **
 
 }  // namespace
 
+namespace {
+
+// shared by ecspmv_decode (FP16 images, 16-bit values out) and ecspmv_decode_f32 (FP32 images, 32-bit values out)
+template <typename T>
+int decode_t(const ecspmv_matrix *A, int value_bits, int64_t *nnz, int32_t *rows, int32_t *cols, T *vals)
+{
+    if (!A || !nnz) return ECSPMV_ERR_INVALID;
+    if (A->image.value_bits != value_bits) return ECSPMV_ERR_INVALID;
+    try {
+        ecs::Triples t;
+        if (ecs::walk_image(A->image, &t, nullptr)) return ECSPMV_ERR_INVALID;
+        const int64_t count = (int64_t)t.rows.size();
+        if (!rows && !cols && !vals) {
+            *nnz = count;
+            return ECSPMV_OK;
+        }
+        if (!rows || !cols || !vals) return ECSPMV_ERR_INVALID;
+        if (*nnz < count) return ECSPMV_ERR_TOO_SMALL;
+        if (count) {
+            std::memcpy(rows, t.rows.data(), sizeof(int32_t) * (size_t)count);
+            std::memcpy(cols, t.cols.data(), sizeof(int32_t) * (size_t)count);
+            for (int64_t i = 0; i < count; ++i) vals[i] = (T)t.vals[(size_t)i];
+        }
+        *nnz = count;
+        return ECSPMV_OK;
+    } catch (const std::bad_alloc &) {
+        return ECSPMV_ERR_NOMEM;
+    }
+}
+
+}  // namespace
+
 extern "C" {
 
 int ecspmv_build_dense(const uint16_t *W, int64_t m, int64_t n, int64_t ld, const ecspmv_build_opts *opts,
@@ -121,6 +153,41 @@ int ecspmv_build_csr(const int64_t *rowptr, const int32_t *col, const uint16_t *
     }
 }
 
+int ecspmv_build_dense_f32(const float *W, int64_t m, int64_t n, int64_t ld, const ecspmv_build_opts *opts,
+                           ecspmv_matrix **out)
+{
+    if (!W || !out || m <= 0 || n <= 0 || ld < n) return ECSPMV_ERR_INVALID;
+    if (n > 65535 || m > 0x7fffffff) return ECSPMV_ERR_UNSUPPORTED;
+    ecs::BuildParams bp;
+    int s = parse_opts(opts, bp);
+    if (s) return s;
+    try {
+        ecs::Csr A;
+        ecs::csr_from_dense_f32(reinterpret_cast<const uint32_t *>(W), m, n, ld, bp.num_threads, A);
+        return finish_build(A, bp, out);
+    } catch (const std::bad_alloc &) {
+        return ECSPMV_ERR_NOMEM;
+    }
+}
+
+int ecspmv_build_csr_f32(const int64_t *rowptr, const int32_t *col, const float *val, int64_t m, int64_t n,
+                         const ecspmv_build_opts *opts, ecspmv_matrix **out)
+{
+    if (!rowptr || !out || m <= 0 || n <= 0) return ECSPMV_ERR_INVALID;
+    if (rowptr[m] < 0 || (rowptr[m] > 0 && (!col || !val))) return ECSPMV_ERR_INVALID;
+    if (n > 65535 || m > 0x7fffffff) return ECSPMV_ERR_UNSUPPORTED;
+    ecs::BuildParams bp;
+    int s = parse_opts(opts, bp);
+    if (s) return s;
+    try {
+        ecs::Csr A;
+        if (ecs::csr_from_csr_f32(rowptr, col, reinterpret_cast<const uint32_t *>(val), m, n, A)) return ECSPMV_ERR_INVALID;
+        return finish_build(A, bp, out);
+    } catch (const std::bad_alloc &) {
+        return ECSPMV_ERR_NOMEM;
+    }
+}
+
 void ecspmv_destroy(ecspmv_matrix *A) { delete A; }
 
 int ecspmv_stats(const ecspmv_matrix *A, ecspmv_stats_t *st)
@@ -135,27 +202,12 @@ int ecspmv_stats(const ecspmv_matrix *A, ecspmv_stats_t *st)
 
 int ecspmv_decode(const ecspmv_matrix *A, int64_t *nnz, int32_t *rows, int32_t *cols, uint16_t *vals)
 {
-    if (!A || !nnz) return ECSPMV_ERR_INVALID;
-    try {
-        ecs::Triples t;
-        if (ecs::walk_image(A->image, &t, nullptr)) return ECSPMV_ERR_INVALID;
-        const int64_t count = (int64_t)t.rows.size();
-        if (!rows && !cols && !vals) {
-            *nnz = count;
-            return ECSPMV_OK;
-        }
-        if (!rows || !cols || !vals) return ECSPMV_ERR_INVALID;
-        if (*nnz < count) return ECSPMV_ERR_TOO_SMALL;
-        if (count) {
-            std::memcpy(rows, t.rows.data(), sizeof(int32_t) * (size_t)count);
-            std::memcpy(cols, t.cols.data(), sizeof(int32_t) * (size_t)count);
-            std::memcpy(vals, t.vals.data(), sizeof(uint16_t) * (size_t)count);
-        }
-        *nnz = count;
-        return ECSPMV_OK;
-    } catch (const std::bad_alloc &) {
-        return ECSPMV_ERR_NOMEM;
-    }
+    return decode_t<uint16_t>(A, 16, nnz, rows, cols, vals);
+}
+
+int ecspmv_decode_f32(const ecspmv_matrix *A, int64_t *nnz, int32_t *rows, int32_t *cols, float *vals)
+{
+    return decode_t<uint32_t>(A, 32, nnz, rows, cols, reinterpret_cast<uint32_t *>(vals));
 }
 
 int ecspmv_block_sets(const ecspmv_matrix *A, int64_t *n_units, int64_t *n_rows, int32_t *g, int32_t *unit_rows,
@@ -221,17 +273,21 @@ int ecspmv_run_batch(const ecspmv_matrix *const *As, const void *const *d_xs, vo
     if (!As || !d_xs || !d_ys || count <= 0) return ECSPMV_ERR_INVALID;
     for (int32_t i = 0; i < count; ++i) {
         if (!As[i] || !d_xs[i] || !d_ys[i]) return ECSPMV_ERR_INVALID;
-        if ((reinterpret_cast<uintptr_t>(d_xs[i]) & 1) || (reinterpret_cast<uintptr_t>(d_ys[i]) & 1))
+        const uintptr_t align = (uintptr_t)(As[i]->image.value_bits / 8 - 1);       // x, y: 2- or 4-byte aligned
+        if ((reinterpret_cast<uintptr_t>(d_xs[i]) & align) || (reinterpret_cast<uintptr_t>(d_ys[i]) & align))
             return ECSPMV_ERR_INVALID;
         if (!As[i]->d_image) return ECSPMV_ERR_NOT_UPLOADED;
     }
     std::vector<int32_t> order((size_t)count);
     for (int32_t i = 0; i < count; ++i) order[(size_t)i] = i;
-    // one launch per run of up to ECS_MAX_BATCH matrices with the same delta width
+    // one launch per run of up to ECS_MAX_BATCH matrices with the same delta width and value width
     for (int32_t base = 0, nb = 0; base < count; base += nb) {
         const int bits = As[order[(size_t)base]]->image.delta_bits;
-        for (nb = 1; base + nb < count && nb < ECS_MAX_BATCH; ++nb)
-            if (As[order[(size_t)(base + nb)]]->image.delta_bits != bits) break;
+        const int vbits = As[order[(size_t)base]]->image.value_bits;
+        for (nb = 1; base + nb < count && nb < ECS_MAX_BATCH; ++nb) {
+            const ecs::Image &nx = As[order[(size_t)(base + nb)]]->image;
+            if (nx.delta_bits != bits || nx.value_bits != vbits) break;
+        }
         ecs::EcsBatch b;
         std::memset(&b, 0, sizeof(b));
         b.count = (uint32_t)nb;
@@ -246,7 +302,7 @@ int ecspmv_run_batch(const ecspmv_matrix *const *As, const void *const *d_xs, vo
             it.n = (uint32_t)im.n;
             it.panel_stride = im.panel_stride;
             it.meta_stride = im.meta_stride;
-            it.x_bytes = ((uint32_t)im.n * 2u + 15u) / 16u * 16u;
+            it.x_bytes = ((uint32_t)im.n * (uint32_t)(vbits / 8) + 15u) / 16u * 16u;
             blocks += (uint32_t)im.num_panels;
             it.block_end = blocks;
             lds = im.lds_bytes > lds ? im.lds_bytes : lds;
@@ -259,7 +315,7 @@ int ecspmv_run_batch(const ecspmv_matrix *const *As, const void *const *d_xs, vo
             const int t = As[order[(size_t)(base + i)]]->image.threads_per_wg;
             if (t) threads = (uint32_t)t;                      // a build-time choice overrides
         }
-        int s = hip_status(ecs::launch_ecspmv(b, threads, lds, mask, (uint32_t)bits, stream));
+        int s = hip_status(ecs::launch_ecspmv(b, threads, lds, mask, (uint32_t)bits, (uint32_t)vbits, stream));
         if (s) return s;
     }
     return ECSPMV_OK;
@@ -278,6 +334,7 @@ int ecspmv_run_multi(const ecspmv_matrix *A, const void *d_X, void *d_Y, int32_t
     if ((reinterpret_cast<uintptr_t>(d_X) & 1) || (reinterpret_cast<uintptr_t>(d_Y) & 1)) return ECSPMV_ERR_INVALID;
     if (!A->d_image) return ECSPMV_ERR_NOT_UPLOADED;
     const ecs::Image &im = A->image;
+    if (im.value_bits != 16) return ECSPMV_ERR_UNSUPPORTED;           // FP16 images only
     if (im.type_mask & ~3u) return ECSPMV_ERR_UNSUPPORTED;            // 8- or 16-grained sets: registers run out
     const uint32_t x_bytes = ((uint32_t)im.n * 2u * (uint32_t)nb + 15u) / 16u * 16u;
     const uint32_t slot_bytes = (im.max_slots * 4u * (uint32_t)nb + 15u) / 16u * 16u;
@@ -318,7 +375,7 @@ int ecspmv_csr_build_dense(const uint16_t *W, int64_t m, int64_t n, int64_t ld, 
         c->rowptr.resize((size_t)m + 1);
         for (int64_t i = 0; i <= m; ++i) c->rowptr[(size_t)i] = (int32_t)A.rowptr[(size_t)i];
         c->col.swap(A.col);
-        c->val.swap(A.val);
+        c->val.assign(A.val.begin(), A.val.end());                 // FP16 bit patterns out of their 32-bit containers
         auto up = [](size_t v) { return (v + 255) / 256 * 256; };
         c->off_col = up(4 * ((size_t)m + 1));
         c->off_val = c->off_col + up(4 * (size_t)c->nnz);

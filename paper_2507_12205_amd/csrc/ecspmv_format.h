@@ -17,6 +17,10 @@
 // values); 64 lane units form a chunk that one wavefront decodes with a prefix scan over lane totals.  Every lane
 // unit leaves one FP32 partial sum in LDS; a row's lane units are consecutive, so the row's sum is a range of them.
 //
+// Value width: `value_bits` of the image header is 16 or 32 (the paper's two precisions).  With FP32 every value
+// array is twice as long and a 128-bit load holds 4 values instead of 8: a unit has 256*g value bytes (the k-th load
+// of lane j still at k*256 + j*16), a lane unit 64 (four loads per lane instead of two); x and y are FP32 as well.
+//
 // Delta width (Section 6.2, EC-CSR-8 / EC-CSR-4 of Section 8.2): `delta_bits` of the image header is 8 or 4.
 // With 4 bits two deltas share a byte, the earlier one in the low nibble; a unit then has 32 delta bytes (2 per
 // lane), a lane unit 8 and a residual chunk 512; the largest delta is 15 and everything else is unchanged.
@@ -81,7 +85,7 @@ typedef struct EcsImageHeader {
     uint32_t panel_stride, meta_stride;
     uint32_t max_slots, lds_bytes;
     uint64_t image_bytes, nnz;
-    uint32_t delta_bits, reserved_;
+    uint32_t delta_bits, value_bits;   /* value_bits: 16 (FP16 values, x, y) or 32 (FP32) */
 } EcsImageHeader;
 
 #endif

@@ -52,27 +52,35 @@ static int resolve_threads(int req)
 // CSR input
 // ------------------------------------------------------------------------------------------------------
 
-int csr_from_dense(const uint16_t *W, int64_t m, int64_t n, int64_t ld, int threads, Csr &out)
+namespace {
+
+// an entry is stored iff it is neither +0 nor -0
+inline bool stored16(uint16_t v) { return (v & 0x7FFFu) != 0; }
+inline bool stored32(uint32_t v) { return (v & 0x7FFFFFFFu) != 0; }
+
+template <typename T, typename Stored>
+int csr_from_dense_t(const T *W, int64_t m, int64_t n, int64_t ld, int threads, int value_bits, Stored stored, Csr &out)
 {
     out.m = m;
     out.n = n;
+    out.value_bits = value_bits;
     out.rowptr.assign((size_t)m + 1, 0);
     std::vector<int64_t> cnt((size_t)m, 0);
     threads = resolve_threads(threads);
     parallel_for(m, threads, [&](int64_t i) {
-        const uint16_t *row = W + i * ld;
+        const T *row = W + i * ld;
         int64_t c = 0;
-        for (int64_t j = 0; j < n; ++j) c += (row[j] & 0x7FFF) != 0;
+        for (int64_t j = 0; j < n; ++j) c += stored(row[j]);
         cnt[(size_t)i] = c;
     });
     for (int64_t i = 0; i < m; ++i) out.rowptr[(size_t)i + 1] = out.rowptr[(size_t)i] + cnt[(size_t)i];
     out.col.resize((size_t)out.rowptr[(size_t)m]);
     out.val.resize((size_t)out.rowptr[(size_t)m]);
     parallel_for(m, threads, [&](int64_t i) {
-        const uint16_t *row = W + i * ld;
+        const T *row = W + i * ld;
         int64_t p = out.rowptr[(size_t)i];
         for (int64_t j = 0; j < n; ++j)
-            if ((row[j] & 0x7FFF) != 0) {
+            if (stored(row[j])) {
                 out.col[(size_t)p] = (int32_t)j;
                 out.val[(size_t)p] = row[j];
                 ++p;
@@ -81,11 +89,14 @@ int csr_from_dense(const uint16_t *W, int64_t m, int64_t n, int64_t ld, int thre
     return 0;
 }
 
-int csr_from_csr(const int64_t *rowptr, const int32_t *col, const uint16_t *val, int64_t m, int64_t n, Csr &out)
+template <typename T, typename Stored>
+int csr_from_csr_t(const int64_t *rowptr, const int32_t *col, const T *val, int64_t m, int64_t n, int value_bits,
+                   Stored stored, Csr &out)
 {
     if (rowptr[0] != 0) return -1;
     out.m = m;
     out.n = n;
+    out.value_bits = value_bits;
     out.rowptr.assign((size_t)m + 1, 0);
     out.col.clear();
     out.val.clear();
@@ -98,7 +109,7 @@ int csr_from_csr(const int64_t *rowptr, const int32_t *col, const uint16_t *val,
             int64_t c = col[p];
             if (c < 0 || c >= n || c <= prev) return -1;
             prev = c;
-            if ((val[p] & 0x7FFF) != 0) {
+            if (stored(val[p])) {
                 out.col.push_back((int32_t)c);
                 out.val.push_back(val[p]);
             }
@@ -106,6 +117,25 @@ int csr_from_csr(const int64_t *rowptr, const int32_t *col, const uint16_t *val,
         out.rowptr[(size_t)i + 1] = (int64_t)out.col.size();
     }
     return 0;
+}
+
+}  // namespace
+
+int csr_from_dense(const uint16_t *W, int64_t m, int64_t n, int64_t ld, int threads, Csr &out)
+{
+    return csr_from_dense_t(W, m, n, ld, threads, 16, stored16, out);
+}
+int csr_from_dense_f32(const uint32_t *W, int64_t m, int64_t n, int64_t ld, int threads, Csr &out)
+{
+    return csr_from_dense_t(W, m, n, ld, threads, 32, stored32, out);
+}
+int csr_from_csr(const int64_t *rowptr, const int32_t *col, const uint16_t *val, int64_t m, int64_t n, Csr &out)
+{
+    return csr_from_csr_t(rowptr, col, val, m, n, 16, stored16, out);
+}
+int csr_from_csr_f32(const int64_t *rowptr, const int32_t *col, const uint32_t *val, int64_t m, int64_t n, Csr &out)
+{
+    return csr_from_csr_t(rowptr, col, val, m, n, 32, stored32, out);
 }
 
 // ------------------------------------------------------------------------------------------------------
@@ -307,11 +337,11 @@ void extract_panel(const Csr &A, int64_t row0, int nrows, int max_g, int max_rou
 }
 
 // value of W[row, col] (must be a stored entry)
-inline uint16_t value_at(const Csr &A, int64_t row, int32_t col)
+inline uint32_t value_at(const Csr &A, int64_t row, int32_t col)
 {
     const int32_t *b = A.col.data() + A.rowptr[row], *e = A.col.data() + A.rowptr[row + 1];
     const int32_t *p = std::lower_bound(b, e, col);
-    return (p != e && *p == col) ? A.val[(size_t)(p - A.col.data())] : (uint16_t)0;
+    return (p != e && *p == col) ? A.val[(size_t)(p - A.col.data())] : 0u;
 }
 
 struct PanelImage {
@@ -352,6 +382,14 @@ void encode_panel(const Csr &A, int64_t row0, int nrows, PanelUnits &pu, bool re
 {
     const int32_t max_delta = (int32_t)ECS_MAX_DELTA(delta_bits);
     const uint32_t unit_db = ECS_UNIT_DBYTES(delta_bits), lane_db = ECS_LANE_DBYTES(delta_bits);
+    const uint32_t vw = (uint32_t)A.value_bits / 8u;      // bytes per value
+    const uint32_t ep = 16u / vw;                         // values per 128-bit load
+    auto put_val = [vw](uint8_t *base, size_t idx, uint32_t v) {
+        if (vw == 2)
+            reinterpret_cast<uint16_t *>(base)[idx] = (uint16_t)v;
+        else
+            reinterpret_cast<uint32_t *>(base)[idx] = v;
+    };
     // ---- ordering (Section 5): sets by decreasing granularity (fixed by the layout); inside a set the
     // units of longer blocks first.
     if (reorder)
@@ -362,7 +400,7 @@ void encode_panel(const Csr &A, int64_t row0, int nrows, PanelUnits &pu, bool re
     // ---- residual rows -> elements (delta, value) with gap fillers and tail padding -> lane units
     struct LaneUnit {
         uint8_t d[ECS_LANE_ELEMS];
-        uint16_t v[ECS_LANE_ELEMS];
+        uint32_t v[ECS_LANE_ELEMS];
         int row;          // panel-local
         int32_t before;   // column "before" the first element: col0 for a row's first unit (its delta is 0)
         uint32_t total;   // sum of the 16 deltas
@@ -372,7 +410,7 @@ void encode_panel(const Csr &A, int64_t row0, int nrows, PanelUnits &pu, bool re
         const std::vector<int32_t> &cols = pu.resid[r];
         if (cols.empty()) continue;
         std::vector<uint8_t> ds;
-        std::vector<uint16_t> vs;
+        std::vector<uint32_t> vs;
         int32_t cur = cols[0];
         ds.push_back(0);
         vs.push_back(value_at(A, row0 + r, cols[0]));
@@ -491,18 +529,18 @@ void encode_panel(const Csr &A, int64_t row0, int nrows, PanelUnits &pu, bool re
         hdr[PH_BD_OFF + t] = off;
         off += unit_db * nu;              // multiple of 16
         hdr[PH_BV_OFF + t] = off;
-        off += 128u * g * nu;
+        off += 64u * vw * g * nu;
         img.delta_bytes += (int64_t)unit_db * nu;
-        img.value_bytes += 128ll * g * nu;
+        img.value_bytes += 64ll * vw * g * nu;
         img.units_by_g[t + 1] = nu;
         img.nnz_by_g[t + 1] = (int64_t)nu * ECS_UNIT_COLS * g;
     }
     hdr[PH_RD_OFF] = off;
     off = align_up(off + lane_db * nlanes, 16);
     hdr[PH_RV_OFF] = off;
-    off += 32u * nlanes;
+    off += 16u * vw * nlanes;
     img.delta_bytes += (int64_t)lane_db * nlanes;
-    img.value_bytes += 32ll * nlanes;
+    img.value_bytes += 16ll * vw * nlanes;
     off = align_up(off, 256);
     hdr[PH_PANEL_BYTES] = off;
     img.bytes.assign(off, 0);
@@ -512,7 +550,7 @@ void encode_panel(const Csr &A, int64_t row0, int nrows, PanelUnits &pu, bool re
     for (int t = ECS_NUM_BTYPES - 1; t >= 0; --t) {
         const uint32_t g = 2u << t;
         uint16_t *utab = (uint16_t *)(P + hdr[PH_UTAB_OFF + t]);
-        std::vector<uint16_t> flat(ECS_UNIT_COLS * g);
+        std::vector<uint32_t> flat(ECS_UNIT_COLS * g);
         for (size_t u = 0; u < pu.units[t].size(); ++u) {
             const PanelUnits::U &un = pu.units[t][u];
             uint16_t *ue = utab + u * (1 + g);
@@ -524,11 +562,12 @@ void encode_panel(const Csr &A, int64_t row0, int nrows, PanelUnits &pu, bool re
                 put_delta(d, k, delta_bits, (uint32_t)(un.cols[k] - un.cols[k - 1]));
             for (unsigned k = 0; k < ECS_UNIT_COLS; ++k)
                 for (uint32_t r = 0; r < g; ++r) flat[k * g + r] = value_at(A, row0 + un.rows[r], un.cols[k]);
-            // permutation: lane j owns flat[4*j*g, 4*(j+1)*g); its k-th group of 8 halfs goes to k*128 + 8*j
-            uint16_t *v = (uint16_t *)(P + hdr[PH_BV_OFF + t] + 128u * g * u);
+            // permutation: lane j owns flat[4*j*g, 4*(j+1)*g); its k-th 128-bit group (8 halfs or 4 floats) goes
+            // to byte k*256 + 16*j of the unit
+            uint8_t *v = P + hdr[PH_BV_OFF + t] + 64u * vw * g * u;
             for (uint32_t j = 0; j < 16; ++j)
-                for (uint32_t k = 0; k < g / 2; ++k)
-                    for (uint32_t i = 0; i < 8; ++i) v[k * 128 + 8 * j + i] = flat[4 * j * g + 8 * k + i];
+                for (uint32_t k = 0; k < 4 * g / ep; ++k)
+                    for (uint32_t i = 0; i < ep; ++i) put_val(v, k * 16 * ep + ep * j + i, flat[4 * j * g + ep * k + i]);
         }
     }
 
@@ -536,14 +575,12 @@ void encode_panel(const Csr &A, int64_t row0, int nrows, PanelUnits &pu, bool re
     for (uint32_t c = 0; c < nchunks; ++c) {
         const uint32_t nl = rchunks[c].nlanes;
         uint8_t *d = P + hdr[PH_RD_OFF] + ECS_CHUNK_DBYTES(delta_bits) * c;
-        uint16_t *v = (uint16_t *)(P + hdr[PH_RV_OFF] + 2048u * c);
+        uint8_t *v = P + hdr[PH_RV_OFF] + 1024u * vw * c;
         for (uint32_t l = 0; l < nl; ++l) {
             const LaneUnit &lu = lanes[c * ECS_CHUNK_LANES + l];
             for (uint32_t i = 0; i < ECS_LANE_ELEMS; ++i) put_delta(d + lane_db * l, i, delta_bits, lu.d[i]);
-            for (uint32_t i = 0; i < 8; ++i) {
-                v[8 * l + i] = lu.v[i];                 // first 128-bit load of lane l
-                v[8 * nl + 8 * l + i] = lu.v[8 + i];    // second
-            }
+            for (uint32_t k = 0; k < ECS_LANE_ELEMS / ep; ++k)          // k-th 128-bit load of lane l
+                for (uint32_t i = 0; i < ep; ++i) put_val(v, ep * nl * k + ep * l + i, lu.v[ep * k + i]);
         }
     }
     for (int r = 0; r < nrows; ++r)
@@ -640,10 +677,11 @@ int build_image(const Csr &A, const BuildParams &bp, Image &out)
     out.num_panels = P;
     out.threads_per_wg = bp.threads_per_wg;
     out.delta_bits = bp.delta_bits;
+    out.value_bits = A.value_bits;
     out.panel_stride = stride;
     out.meta_stride = meta;
     out.max_slots = slots;
-    const uint32_t x_bytes = align_up((uint32_t)n * 2u, 16);
+    const uint32_t x_bytes = align_up((uint32_t)n * (uint32_t)(A.value_bits / 8), 16);
     out.lds_bytes = x_bytes + meta + align_up(slots * 4u, 16);
 
     ecspmv_stats_t &st = out.stats;
@@ -653,8 +691,9 @@ int build_image(const Csr &A, const BuildParams &bp, Image &out)
     st.n = n;
     st.nnz = nnz;
     st.image_bytes = (int64_t)total;
-    st.csr32_bytes = 6 * nnz + 4 * (m + 1);
-    st.csr16_bytes = 4 * nnz + 4 * (m + 1);
+    st.csr32_bytes = (4 + A.value_bits / 8) * nnz + 4 * (m + 1);
+    st.csr16_bytes = (2 + A.value_bits / 8) * nnz + 4 * (m + 1);
+    st.value_bits = A.value_bits;
     st.num_panels = P;
     st.threads_per_wg = bp.threads_per_wg;
     st.delta_bits = bp.delta_bits;
@@ -700,6 +739,7 @@ int build_image(const Csr &A, const BuildParams &bp, Image &out)
     ih.image_bytes = total;
     ih.nnz = (uint64_t)nnz;
     ih.delta_bits = (uint32_t)bp.delta_bits;
+    ih.value_bits = (uint32_t)A.value_bits;
     std::memcpy(out.bytes.data(), &ih, sizeof(ih));
     st.build_seconds = std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count();
     return 0;
@@ -730,6 +770,12 @@ int walk_image(const Image &im, Triples *tri, BlockSets *bs)
 {
     const uint8_t *base = im.bytes.data() + ECS_IMAGE_HEADER;
     const int bits = im.delta_bits;
+    const uint32_t vw = (uint32_t)im.value_bits / 8u, ep = 16u / vw;
+    auto get_val = [vw](const uint8_t *base, size_t idx) -> uint32_t {
+        return vw == 2 ? (uint32_t)reinterpret_cast<const uint16_t *>(base)[idx]
+                       : reinterpret_cast<const uint32_t *>(base)[idx];
+    };
+    const uint32_t absmask = vw == 2 ? 0x7FFFu : 0x7FFFFFFFu;
     for (int p = 0; p < im.num_panels; ++p) {
         PanelView pv;
         pv.P = base + (size_t)im.panel_stride * p;
@@ -743,7 +789,7 @@ int walk_image(const Image &im, Triples *tri, BlockSets *bs)
             for (uint32_t u = 0; u < nu; ++u) {
                 const uint16_t *ue = utab + u * (1 + g);
                 const uint8_t *d = pv.P + pv.hdr[PH_BD_OFF + t] + ECS_UNIT_DBYTES(bits) * u;
-                const uint16_t *v = (const uint16_t *)(pv.P + pv.hdr[PH_BV_OFF + t] + 128u * g * u);
+                const uint8_t *v = pv.P + pv.hdr[PH_BV_OFF + t] + 64u * vw * g * u;
                 int32_t cols[ECS_UNIT_COLS];
                 // 16 lanes x 4 columns: local prefix inside a lane, exclusive scan over lanes, plus base
                 uint32_t lane_excl = 0;
@@ -767,12 +813,12 @@ int walk_image(const Image &im, Triples *tri, BlockSets *bs)
                 }
                 if (tri)
                     for (uint32_t j = 0; j < 16; ++j)
-                        for (uint32_t k = 0; k < g / 2; ++k)
-                            for (uint32_t i = 0; i < 8; ++i) {
-                                const uint32_t f = 8 * k + i;          // index in lane j's run
+                        for (uint32_t k = 0; k < 4 * g / ep; ++k)
+                            for (uint32_t i = 0; i < ep; ++i) {
+                                const uint32_t f = ep * k + i;         // index in lane j's run
                                 const uint32_t c = f / g, r = f % g;
-                                const uint16_t val = v[k * 128 + 8 * j + i];
-                                if ((val & 0x7FFF) == 0) continue;
+                                const uint32_t val = get_val(v, k * 16 * ep + ep * j + i);
+                                if ((val & absmask) == 0) continue;
                                 tri->rows.push_back((int32_t)(row0 + rows[r]));
                                 tri->cols.push_back(cols[4 * j + c]);
                                 tri->vals.push_back(val);
@@ -788,7 +834,7 @@ int walk_image(const Image &im, Triples *tri, BlockSets *bs)
             const uint32_t nl = std::min<uint32_t>(ECS_CHUNK_LANES, nlanes - c * ECS_CHUNK_LANES);
             if (rch[c].nlanes != nl || !(rch[c].head_mask & 1)) return -101;
             const uint8_t *d = pv.P + pv.hdr[PH_RD_OFF] + ECS_CHUNK_DBYTES(bits) * c;
-            const uint16_t *v = (const uint16_t *)(pv.P + pv.hdr[PH_RV_OFF] + 2048u * c);
+            const uint8_t *v = pv.P + pv.hdr[PH_RV_OFF] + 1024u * vw * c;
             int64_t excl = 0;
             for (uint32_t l = 0; l < nl; ++l) {
                 const uint64_t below = rch[c].head_mask & ((l == 63) ? ~0ull : ((2ull << l) - 1));
@@ -800,8 +846,8 @@ int walk_image(const Image &im, Triples *tri, BlockSets *bs)
                 int64_t rel = 0;
                 for (uint32_t k = 0; k < ECS_LANE_ELEMS; ++k) {
                     rel += get_delta(d + ECS_LANE_DBYTES(bits) * l, k, bits);
-                    const uint16_t val = (k < 8) ? v[8 * l + k] : v[8 * nl + 8 * l + (k - 8)];
-                    if ((val & 0x7FFF) == 0) continue;
+                    const uint32_t val = get_val(v, ep * nl * (k / ep) + ep * l + (k % ep));
+                    if ((val & absmask) == 0) continue;
                     tri->rows.push_back((int32_t)(row0 + row));
                     tri->cols.push_back((int32_t)(e.c + excl + rel));
                     tri->vals.push_back(val);

@@ -92,10 +92,13 @@ __device__ __forceinline__ float fma_h(uint32_t w_bits, float xf, float acc)
 }
 
 // the NB right-hand sides of one column sit side by side in LDS (x[col * NB + b]): one LDS read fetches them all
-template <int NB>
+template <int NB, int VW>
 __device__ __forceinline__ void gather_x(const uint16_t *xs, uint32_t col, float (&xv)[NB])
 {
-    if constexpr (NB == 1) {
+    if constexpr (VW == 4) {
+        static_assert(NB == 1, "several right-hand sides are built for FP16 only");
+        xv[0] = reinterpret_cast<const float *>(xs)[col];
+    } else if constexpr (NB == 1) {
         xv[0] = half_bits_to_float(xs[col]);
     } else if constexpr (NB == 2) {
         const uint32_t w = *reinterpret_cast<const uint32_t *>(xs + 2u * col);
@@ -149,34 +152,35 @@ struct Ctx {
 
 // ---- g >= 2 block sets: a DPP row of 16 lanes takes one unit (64 columns), 4 columns per lane; a wavefront
 // takes a chunk of 4 consecutive units.  DB = width of a delta index in bits (8 or 4).
-template <int G>
+// VW = bytes per value: 2 (FP16) or 4 (FP32)
+template <int G, int VW>
 struct UnitRegs {
     uint32_t d;            // 4 deltas: 4 bytes, or 4 nibbles in the low half
-    uint4 v[G / 2];        // 4 * G FP16 values of this lane
+    uint4 v[G * VW / 4];   // 4 * G values of this lane
 };
 
 // Unconditional: DPP rows beyond the last unit of the set re-read that last unit (and ignore it), so that the
 // number of loads in flight never depends on data and waits can name exact counts.
-template <int G, int DB>
+template <int G, int DB, int VW>
 __device__ __forceinline__ void load_unit(const Ctx &c, uint32_t bd_off, uint32_t bv_off, uint32_t u, uint32_t nu,
-                                          UnitRegs<G> &r)
+                                          UnitRegs<G, VW> &r)
 {
     const uint32_t j = c.lane & 15;
     const uint32_t uu = min(u, nu - 1u);
     // one 32-bit offset from the (wave-uniform) panel pointer per load: scalar base + vector offset addressing
     const uint32_t od = bd_off + (8u * DB) * uu + (DB / 2u) * j;
-    const uint32_t ov = bv_off + (128u * G) * uu + 16u * j;
+    const uint32_t ov = bv_off + (64u * VW * G) * uu + 16u * j;
     if constexpr (DB == 8)
         r.d = load4(c.panel + od);
     else
         r.d = load2(c.panel + od);
 #pragma unroll
-    for (int k = 0; k < G / 2; ++k) r.v[k] = load16(c.panel + (ov + 256u * k));
+    for (int k = 0; k < G * VW / 4; ++k) r.v[k] = load16(c.panel + (ov + 256u * k));
 }
 
-template <int G, int DB, int NB>
+template <int G, int DB, int NB, int VW>
 __device__ __forceinline__ void compute_unit(const Ctx &c, const uint16_t *utab, uint32_t u, uint32_t nu,
-                                             const UnitRegs<G> &r)
+                                             const UnitRegs<G, VW> &r)
 {
     const uint32_t j = c.lane & 15;
     const bool active = u < nu;
@@ -193,7 +197,7 @@ __device__ __forceinline__ void compute_unit(const Ctx &c, const uint16_t *utab,
     const uint32_t start = (uint32_t)ue[0] + (uint32_t)incl - rel[3];
     float xv[4][NB];
 #pragma unroll
-    for (int k = 0; k < 4; ++k) gather_x<NB>(c.xs, start + rel[k], xv[k]);
+    for (int k = 0; k < 4; ++k) gather_x<NB, VW>(c.xs, start + rel[k], xv[k]);
     float acc[G][NB];
 #pragma unroll
     for (int q = 0; q < G; ++q)
@@ -201,11 +205,18 @@ __device__ __forceinline__ void compute_unit(const Ctx &c, const uint16_t *utab,
         for (int b = 0; b < NB; ++b) acc[q][b] = 0.0f;
 #pragma unroll
     for (int f = 0; f < 4 * G; ++f) {                              // f = column * G + row
-        const uint4 q = r.v[f >> 3];
-        const uint32_t word = ((f >> 1) & 3) == 0 ? q.x : ((f >> 1) & 3) == 1 ? q.y : ((f >> 1) & 3) == 2 ? q.z : q.w;
-        const uint32_t hb = (f & 1) ? (word >> 16) : (word & 0xFFFF);
+        if constexpr (VW == 2) {
+            const uint4 q = r.v[f >> 3];
+            const uint32_t word = ((f >> 1) & 3) == 0 ? q.x : ((f >> 1) & 3) == 1 ? q.y : ((f >> 1) & 3) == 2 ? q.z : q.w;
+            const uint32_t hb = (f & 1) ? (word >> 16) : (word & 0xFFFF);
 #pragma unroll
-        for (int b = 0; b < NB; ++b) acc[f % G][b] = fma_h(hb, xv[f / G][b], acc[f % G][b]);
+            for (int b = 0; b < NB; ++b) acc[f % G][b] = fma_h(hb, xv[f / G][b], acc[f % G][b]);
+        } else {
+            const uint4 q = r.v[f >> 2];
+            const uint32_t word = (f & 3) == 0 ? q.x : (f & 3) == 1 ? q.y : (f & 3) == 2 ? q.z : q.w;
+#pragma unroll
+            for (int b = 0; b < NB; ++b) acc[f % G][b] = fmaf(__uint_as_float(word), xv[f / G][b], acc[f % G][b]);
+        }
     }
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
@@ -221,9 +232,9 @@ __device__ __forceinline__ void compute_unit(const Ctx &c, const uint16_t *utab,
 // A set's chunks c0, c0 + W, c0 + 2W, ... belong to this wavefront.  DEPTH register buffers take turns: all are
 // requested before anything is computed, and each is refilled right after it has been consumed, so a wavefront
 // always has its next DEPTH chunks on the way (the double buffering of Section 7, deeper and without copies).
-template <int G, int DB, int DEPTH, int NB>
+template <int G, int DB, int DEPTH, int NB, int VW>
 struct BlockSet {
-    UnitRegs<G> buf[DEPTH];
+    UnitRegs<G, VW> buf[DEPTH];
     uint32_t nu, n, c0, bd_off, bv_off;
     const uint16_t *utab;
 
@@ -246,7 +257,7 @@ struct BlockSet {
 #pragma unroll
         for (int d = 0; d < DEPTH; ++d) {
             const bool have = (uint32_t)d < n;
-            load_unit<G, DB>(c, have ? bd_off : 0u, have ? bv_off : 0u, have ? unit_of(c, d) : 0u, have ? nu : 1u, buf[d]);
+            load_unit<G, DB, VW>(c, have ? bd_off : 0u, have ? bv_off : 0u, have ? unit_of(c, d) : 0u, have ? nu : 1u, buf[d]);
         }
     }
     __device__ __forceinline__ void run(const Ctx &c)
@@ -255,41 +266,41 @@ struct BlockSet {
         for (; i + 2 * DEPTH - 1 < n; i += DEPTH) {    // chunks i + DEPTH ... i + 2 DEPTH - 1 exist: unconditional refills
 #pragma unroll
             for (int d = 0; d < DEPTH; ++d) {
-                compute_unit<G, DB, NB>(c, utab, unit_of(c, i + d), nu, buf[d]);
-                load_unit<G, DB>(c, bd_off, bv_off, unit_of(c, i + DEPTH + d), nu, buf[d]);
+                compute_unit<G, DB, NB, VW>(c, utab, unit_of(c, i + d), nu, buf[d]);
+                load_unit<G, DB, VW>(c, bd_off, bv_off, unit_of(c, i + DEPTH + d), nu, buf[d]);
             }
         }
 #pragma unroll
         for (int d = 0; d < DEPTH; ++d) {
             if (i + d < n) {
-                compute_unit<G, DB, NB>(c, utab, unit_of(c, i + d), nu, buf[d]);
-                if (i + DEPTH + d < n) load_unit<G, DB>(c, bd_off, bv_off, unit_of(c, i + DEPTH + d), nu, buf[d]);
+                compute_unit<G, DB, NB, VW>(c, utab, unit_of(c, i + d), nu, buf[d]);
+                if (i + DEPTH + d < n) load_unit<G, DB, VW>(c, bd_off, bv_off, unit_of(c, i + DEPTH + d), nu, buf[d]);
             }
         }
 #pragma unroll
         for (int d = 0; d < DEPTH; ++d)
-            if (i + DEPTH + d < n) compute_unit<G, DB, NB>(c, utab, unit_of(c, i + DEPTH + d), nu, buf[d]);
+            if (i + DEPTH + d < n) compute_unit<G, DB, NB, VW>(c, utab, unit_of(c, i + DEPTH + d), nu, buf[d]);
     }
 };
 
 // ---- residual (1-grained) set: a wavefront takes a chunk of 64 lane units, 16 elements per lane.
-template <int DB>
+template <int DB, int VW>
 struct ChunkRegs {
     uint32_t d[DB / 2]; // 16 deltas: 16 bytes or 16 nibbles
-    uint4 v0, v1;       // 16 FP16 values
+    uint4 v[VW];        // 16 values: two or four 128-bit loads
 };
 
 // Lanes beyond the end of the last chunk load 16 zero bytes the panel keeps for them (zero deltas, zero values), so
 // that the arithmetic needs no masking.  Unconditional, like load_unit.
-template <int DB>
+template <int DB, int VW>
 __device__ __forceinline__ void load_chunk(const Ctx &c, uint32_t rd_off, uint32_t rv_off, uint32_t zero_off, uint32_t ch,
-                                           uint32_t nlanes, ChunkRegs<DB> &r)
+                                           uint32_t nlanes, ChunkRegs<DB, VW> &r)
 {
     const uint32_t nl = min(64u, nlanes - 64u * ch);
     const bool active = c.lane < nl;
     const uint32_t od = active ? rd_off + (128u * DB) * ch + (2u * DB) * c.lane : zero_off;
-    const uint32_t ov = active ? rv_off + 2048u * ch + 16u * c.lane : zero_off;
-    const uint32_t ow = active ? ov + 16u * nl : zero_off;
+    const uint32_t ov = active ? rv_off + (1024u * VW) * ch + 16u * c.lane : zero_off;
+    const uint32_t step = active ? 16u * nl : 0u;          // from one 128-bit load of this lane to its next
     if constexpr (DB == 8) {
         const uint4 t = load16(c.panel + od);
         r.d[0] = t.x, r.d[1] = t.y, r.d[2] = t.z, r.d[3] = t.w;
@@ -297,15 +308,15 @@ __device__ __forceinline__ void load_chunk(const Ctx &c, uint32_t rd_off, uint32
         const uint2 t = load8(c.panel + od);
         r.d[0] = t.x, r.d[1] = t.y;
     }
-    r.v0 = load16(c.panel + ov);
-    r.v1 = load16(c.panel + ow);
+#pragma unroll
+    for (int k = 0; k < VW; ++k) r.v[k] = load16(c.panel + (ov + step * k));
 }
 
 // One partial sum per lane unit goes to LDS (`part`, indexed by the lane unit's position in the residual stream); a
 // row's lane units are consecutive, so the final pass adds a range of them.  No cross-lane reduction is needed here.
-template <int DB, bool FENCE, int NB>
+template <int DB, bool FENCE, int NB, int VW>
 __device__ __forceinline__ void compute_chunk(const Ctx &c, const EcsRChunk *rch, const EcsREntry *ren, float *part,
-                                              uint32_t ch, const ChunkRegs<DB> &r)
+                                              uint32_t ch, const ChunkRegs<DB, VW> &r)
 {
     // lane-local inclusive prefix of the 16 deltas
     uint32_t rel[16];
@@ -325,15 +336,22 @@ __device__ __forceinline__ void compute_chunk(const Ctx &c, const EcsRChunk *rch
     float acc[NB];
 #pragma unroll
     for (int b = 0; b < NB; ++b) acc[b] = 0.0f;
-    const uint32_t vw[8] = {r.v0.x, r.v0.y, r.v0.z, r.v0.w, r.v1.x, r.v1.y, r.v1.z, r.v1.w};
+    uint32_t vw[4 * VW];
+#pragma unroll
+    for (int k = 0; k < VW; ++k) vw[4 * k] = r.v[k].x, vw[4 * k + 1] = r.v[k].y, vw[4 * k + 2] = r.v[k].z, vw[4 * k + 3] = r.v[k].w;
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
-        const uint32_t word = vw[i >> 1];
-        const uint32_t hb = (i & 1) ? (word >> 16) : (word & 0xFFFF);
         float xv[NB];
-        gather_x<NB>(c.xs, (uint32_t)(start + (int)rel[i]), xv);
+        gather_x<NB, VW>(c.xs, (uint32_t)(start + (int)rel[i]), xv);
+        if constexpr (VW == 2) {
+            const uint32_t word = vw[i >> 1];
+            const uint32_t hb = (i & 1) ? (word >> 16) : (word & 0xFFFF);
 #pragma unroll
-        for (int b = 0; b < NB; ++b) acc[b] = fma_h(hb, xv[b], acc[b]);
+            for (int b = 0; b < NB; ++b) acc[b] = fma_h(hb, xv[b], acc[b]);
+        } else {
+#pragma unroll
+            for (int b = 0; b < NB; ++b) acc[b] = fmaf(__uint_as_float(vw[i]), xv[b], acc[b]);
+        }
     }
 #pragma unroll
     for (int b = 0; b < NB; ++b) part[(64u * ch + c.lane) * NB + b] = acc[b];
@@ -342,9 +360,9 @@ __device__ __forceinline__ void compute_chunk(const Ctx &c, const EcsRChunk *rch
     if constexpr (FENCE) __builtin_amdgcn_sched_barrier(0);
 }
 
-template <int DB, int DEPTH, bool FENCE, int NB>
+template <int DB, int DEPTH, bool FENCE, int NB, int VW>
 struct ResidualSet {
-    ChunkRegs<DB> buf[DEPTH];
+    ChunkRegs<DB, VW> buf[DEPTH];
     uint32_t nlanes, n, c0, rd_off, rv_off, zero_off;
     const EcsRChunk *rch;
     const EcsREntry *ren;
@@ -367,7 +385,7 @@ struct ResidualSet {
 #pragma unroll
         for (int d = 0; d < DEPTH; ++d) {
             const bool have = (uint32_t)d < n;
-            load_chunk<DB>(c, have ? rd_off : 0u, have ? rv_off : 0u, have ? zero_off : 0u, have ? chunk_of(c, d) : 0u,
+            load_chunk<DB, VW>(c, have ? rd_off : 0u, have ? rv_off : 0u, have ? zero_off : 0u, have ? chunk_of(c, d) : 0u,
                            have ? nlanes : 1u, buf[d]);
         }
     }
@@ -377,28 +395,29 @@ struct ResidualSet {
         for (; i + 2 * DEPTH - 1 < n; i += DEPTH) {
 #pragma unroll
             for (int d = 0; d < DEPTH; ++d) {
-                compute_chunk<DB, FENCE, NB>(c, rch, ren, part, chunk_of(c, i + d), buf[d]);
-                load_chunk<DB>(c, rd_off, rv_off, zero_off, chunk_of(c, i + DEPTH + d), nlanes, buf[d]);
+                compute_chunk<DB, FENCE, NB, VW>(c, rch, ren, part, chunk_of(c, i + d), buf[d]);
+                load_chunk<DB, VW>(c, rd_off, rv_off, zero_off, chunk_of(c, i + DEPTH + d), nlanes, buf[d]);
             }
         }
 #pragma unroll
         for (int d = 0; d < DEPTH; ++d) {
             if (i + d < n) {
-                compute_chunk<DB, FENCE, NB>(c, rch, ren, part, chunk_of(c, i + d), buf[d]);
-                if (i + DEPTH + d < n) load_chunk<DB>(c, rd_off, rv_off, zero_off, chunk_of(c, i + DEPTH + d), nlanes, buf[d]);
+                compute_chunk<DB, FENCE, NB, VW>(c, rch, ren, part, chunk_of(c, i + d), buf[d]);
+                if (i + DEPTH + d < n) load_chunk<DB, VW>(c, rd_off, rv_off, zero_off, chunk_of(c, i + DEPTH + d), nlanes, buf[d]);
             }
         }
 #pragma unroll
         for (int d = 0; d < DEPTH; ++d)
-            if (i + DEPTH + d < n) compute_chunk<DB, FENCE, NB>(c, rch, ren, part, chunk_of(c, i + DEPTH + d), buf[d]);
+            if (i + DEPTH + d < n) compute_chunk<DB, FENCE, NB, VW>(c, rch, ren, part, chunk_of(c, i + DEPTH + d), buf[d]);
     }
 };
 
 // TM: bit t set = the image holds units of granularity 2 << t somewhere (the residual set is always handled);
 // DB: width of the delta indices in bits; BATCH: buffer depths for a launch that carries several SpMVs;
 // K: 16-byte pieces of [tables | x] each thread brings to LDS before the generic loop takes the rest;
-// NB: right-hand sides handled at once (x holds n rows of NB values, y m rows of NB values)
-template <int TM, int DB, bool BATCH, int K, int NB>
+// NB: right-hand sides handled at once (x holds n rows of NB values, y m rows of NB values);
+// VW: bytes per value of W, x and y (2 = FP16, 4 = FP32)
+template <int TM, int DB, bool BATCH, int K, int NB, int VW>
 __global__ __launch_bounds__(1024) ECS_KATTR void ecspmv_kernel(const ecs::EcsBatch batch)
 {
     // which SpMV of the batch this workgroup works for (one item in the plain case)
@@ -410,7 +429,7 @@ __global__ __launch_bounds__(1024) ECS_KATTR void ecspmv_kernel(const ecs::EcsBa
     const ecs::EcsBatchItem &it = batch.item[k];
     const uint16_t *__restrict__ x = it.x;
     uint16_t *__restrict__ y = it.y;
-    const uint32_t n = it.n * NB, meta_stride = it.meta_stride, x_bytes = it.x_bytes;   // n: FP16 entries of x
+    const uint32_t n = it.n * NB * (VW / 2), meta_stride = it.meta_stride, x_bytes = it.x_bytes;   // n: 2-byte units of x
 
     extern __shared__ uint4 lds4[];
     uint8_t *lds = reinterpret_cast<uint8_t *>(lds4);
@@ -467,11 +486,11 @@ __global__ __launch_bounds__(1024) ECS_KATTR void ecspmv_kernel(const ecs::EcsBa
     // and before the tables and x have even reached LDS.
     // buffers per set: deeper where chunks are small and frequent, shallower where registers run out
     constexpr bool wide = (TM & 12) != 0;
-    BlockSet<16, DB, 1, NB> b16;
-    BlockSet<8, DB, 1, NB> b8;
-    BlockSet<4, DB, wide ? 1 : D4, NB> b4;
-    BlockSet<2, DB, wide ? 2 : D2, NB> b2;
-    ResidualSet<DB, wide ? 2 : (TM == 0 && BATCH ? DR0B : DR), BATCH, NB> rs;
+    BlockSet<16, DB, 1, NB, VW> b16;
+    BlockSet<8, DB, 1, NB, VW> b8;
+    BlockSet<4, DB, wide ? 1 : D4, NB, VW> b4;
+    BlockSet<2, DB, wide ? 2 : D2, NB, VW> b2;
+    ResidualSet<DB, wide ? 2 : (TM == 0 && BATCH ? DR0B : DR), BATCH, NB, VW> rs;
     if constexpr ((TM & 8) != 0) b16.prologue(c, hdr, 3);
     if constexpr ((TM & 4) != 0) b8.prologue(c, hdr, 2);
     if constexpr ((TM & 2) != 0) b4.prologue(c, hdr, 1);
@@ -530,7 +549,11 @@ __global__ __launch_bounds__(1024) ECS_KATTR void ecspmv_kernel(const ecs::EcsBa
 #pragma unroll
         for (int b = 0; b < NB; ++b) {
             const float t = row16_allreduce(sum[b]);
-            if (j == 0) y[(row0 + r) * NB + b] = __half_as_ushort(__float2half_rn(t));
+            if constexpr (VW == 2) {
+                if (j == 0) y[(row0 + r) * NB + b] = __half_as_ushort(__float2half_rn(t));
+            } else {
+                if (j == 0) reinterpret_cast<float *>(y)[row0 + r] = t;
+            }
         }
     }
 }
@@ -581,18 +604,18 @@ __global__ __launch_bounds__(1024) void stream_read_kernel(const uint4 *__restri
 
 namespace ecs {
 
-template <int TM, int DB, bool BATCH, int K, int NB>
+template <int TM, int DB, bool BATCH, int K, int NB, int VW = 2>
 static int launch_k(const EcsBatch &batch, uint32_t threads, uint32_t lds_bytes, void *stream)
 {
     static thread_local uint32_t attr_set_for = 0;
     if (lds_bytes > 65536 && lds_bytes > attr_set_for) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(ecspmv_kernel<TM, DB, BATCH, K, NB>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(ecspmv_kernel<TM, DB, BATCH, K, NB, VW>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
         if (e != hipSuccess) return (int)e;
         attr_set_for = lds_bytes;
     }
     const uint32_t grid = batch.item[batch.count - 1].block_end;
-    hipLaunchKernelGGL((ecspmv_kernel<TM, DB, BATCH, K, NB>), dim3(grid), dim3(threads), lds_bytes, (hipStream_t)stream, batch);
+    hipLaunchKernelGGL((ecspmv_kernel<TM, DB, BATCH, K, NB, VW>), dim3(grid), dim3(threads), lds_bytes, (hipStream_t)stream, batch);
     return (int)hipGetLastError();
 }
 
@@ -614,8 +637,13 @@ static int launch_b(const EcsBatch &batch, uint32_t threads, uint32_t lds_bytes,
 }
 
 template <int TM>
-static int launch_tm(const EcsBatch &batch, uint32_t threads, uint32_t lds_bytes, uint32_t delta_bits, void *stream)
+static int launch_tm(const EcsBatch &batch, uint32_t threads, uint32_t lds_bytes, uint32_t delta_bits, uint32_t value_bits,
+                     void *stream)
 {
+    // FP32 values: one variant per set mask and delta width (widest staging, lone-launch buffer depths)
+    if (value_bits == 32)
+        return delta_bits == 4 ? launch_k<TM, 4, false, 4, 1, 4>(batch, threads, lds_bytes, stream)
+                               : launch_k<TM, 8, false, 4, 1, 4>(batch, threads, lds_bytes, stream);
     // only the residual-only kernel has a second set of buffer depths
     if (TM == 0 && batch.count > 1)
         return delta_bits == 4 ? launch_b<TM, 4, TM == 0>(batch, threads, lds_bytes, stream)
@@ -651,16 +679,16 @@ int launch_ecspmv_multi(const EcsBatch &batch, uint32_t threads, uint32_t lds_by
 }
 
 int launch_ecspmv(const EcsBatch &batch, uint32_t threads, uint32_t lds_bytes, uint32_t type_mask, uint32_t delta_bits,
-                  void *stream)
+                  uint32_t value_bits, void *stream)
 {
     // one instantiation per highest granularity present: sets that do not occur cost no registers
     const int top = (type_mask & 8) ? 15 : (type_mask & 4) ? 7 : (type_mask & 2) ? 3 : (type_mask & 1) ? 1 : 0;
     switch (top) {
-    case 15: return launch_tm<15>(batch, threads, lds_bytes, delta_bits, stream);
-    case 7: return launch_tm<7>(batch, threads, lds_bytes, delta_bits, stream);
-    case 3: return launch_tm<3>(batch, threads, lds_bytes, delta_bits, stream);
-    case 1: return launch_tm<1>(batch, threads, lds_bytes, delta_bits, stream);
-    default: return launch_tm<0>(batch, threads, lds_bytes, delta_bits, stream);
+    case 15: return launch_tm<15>(batch, threads, lds_bytes, delta_bits, value_bits, stream);
+    case 7: return launch_tm<7>(batch, threads, lds_bytes, delta_bits, value_bits, stream);
+    case 3: return launch_tm<3>(batch, threads, lds_bytes, delta_bits, value_bits, stream);
+    case 1: return launch_tm<1>(batch, threads, lds_bytes, delta_bits, value_bits, stream);
+    default: return launch_tm<0>(batch, threads, lds_bytes, delta_bits, value_bits, stream);
     }
 }
 

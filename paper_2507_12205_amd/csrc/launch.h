@@ -23,7 +23,7 @@ struct EcsBatch {
 
 // Launches one kernel for all items (count <= ECS_MAX_BATCH, same workgroup size for all).
 int launch_ecspmv(const EcsBatch &batch, uint32_t threads, uint32_t lds_bytes, uint32_t type_mask, uint32_t delta_bits,
-                  void *stream);
+                  uint32_t value_bits, void *stream);
 // One matrix, nb = 2, 4 or 8 right-hand sides (x: n rows of nb values, y: m rows of nb values); type_mask must not
 // have bits above the 4-grained set.
 int launch_ecspmv_multi(const EcsBatch &batch, uint32_t threads, uint32_t lds_bytes, uint32_t type_mask,

@@ -21,8 +21,10 @@ def upload(mat: B.Matrix, device="cuda:0", stream=None) -> torch.Tensor:
 
 
 def run(mat: B.Matrix, x: torch.Tensor, y: torch.Tensor, stream=None) -> torch.Tensor:
-    """y = W x on the given (or current) stream; x, y are FP16 CUDA tensors of length n, m."""
-    assert x.dtype == torch.float16 and y.dtype == torch.float16 and x.is_cuda and y.is_cuda
+    """y = W x on the given (or current) stream; x, y are CUDA tensors of length n, m: FP16, or FP32 for a matrix
+    built from FP32 values."""
+    want = torch.float32 if mat.ecspmv_stats().value_bits == 32 else torch.float16
+    assert x.dtype == want and y.dtype == want and x.is_cuda and y.is_cuda
     assert x.is_contiguous() and y.is_contiguous()
     mat.ecspmv_run(x.data_ptr(), y.data_ptr(), _stream_handle(stream))
     return y
