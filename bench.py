@@ -447,6 +447,59 @@ def main():
         out["multi_rhs"] = {"format": f"EC-CSR-{mats[0][0]['st'].delta_bits}", "panels": 512, "per_shape": multi}
         del mclasses
 
+    if not args.no_extras:
+        # FP32 values (the paper's other precision): the same patterns with FP32 values, x and y; rotation of up to
+        # three copies, one launch each and one launch per step
+        fopts = E.make_opts(max_granularity=args.max_granularity, num_panels=args.panels,
+                            threads_per_wg=args.threads_per_wg, delta_bits=args.delta_bits)
+        ncp = min(copies, 3)
+
+        def make_f32(job):
+            copy, sid = job
+            W = keep_dense[sid][0] if copy == 0 else gen.make_matrix(cfg, sid, seed=0, copy=copy)
+            return copy, sid, E.ecspmv_build_dense_f32(W.astype(np.float32), fopts)
+
+        flayers = [[None] * nshapes for _ in range(ncp)]
+        with ThreadPoolExecutor(max_workers=3) as ex:
+            for copy, sid, A in ex.map(make_f32, [(c, s_) for c in range(ncp) for s_ in range(nshapes)]):
+                D.upload(A, stream=stream)
+                st = A.ecspmv_stats()
+                flayers[copy][sid] = dict(A=A, st=st, x=torch.randn(int(st.n), device="cuda"),
+                                          y=torch.empty(int(st.m), dtype=torch.float32, device="cuda"))
+        fbatch = [E.Batch([e["A"] for e in layer], [e["x"].data_ptr() for e in layer],
+                          [e["y"].data_ptr() for e in layer]) for layer in flayers]
+        fbytes = [sum(int(e["st"].value_bytes + e["st"].delta_bytes + e["st"].meta_bytes + 4 * e["st"].n + 4 * e["st"].m)
+                      for e in layer) for layer in flayers]
+        res = {}
+        for mode in ("single", "all"):
+            def go(layer_i):
+                if mode == "single":
+                    for e in flayers[layer_i]:
+                        e["A"].ecspmv_run(e["x"].data_ptr(), e["y"].data_ptr(), sh)
+                else:
+                    fbatch[layer_i].ecspmv_run_batch(sh)
+            for w in range(ncp):
+                go(w)
+            torch.cuda.synchronize()
+            ev0.record(stream)
+            for s_ in range(args.steps):
+                go(s_ % ncp)
+            ev1.record(stream)
+            torch.cuda.synchronize()
+            ms = ev0.elapsed_time(ev1)
+            mv = sum(fbytes[s_ % ncp] for s_ in range(args.steps))
+            res[mode] = {"us_per_step": round(ms * 1e3 / args.steps, 3), "gbps": round(mv / (ms * 1e-3) / 1e9, 1),
+                         "pct_of_hbm_peak": round(100.0 * mv / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 2)}
+        fnnz = sum(e["st"].nnz for e in flayers[0])
+        fimg = sum(e["st"].image_bytes for e in flayers[0])
+        out["fp32_values"] = {"format": f"EC-CSR-{flayers[0][0]['st'].delta_bits}, FP32 values, x, y", "rotation_copies": ncp,
+                              "bytes_per_nnz": round(fimg / fnnz, 4),
+                              "eccsr_over_csr32": round(fimg / sum(e["st"].csr32_bytes for e in flayers[0]), 4),
+                              "nnz_by_granularity_1_2_4_8_16":
+                                  [int(sum(e["st"].nnz_by_g[k] for e in flayers[0])) for k in range(5)],
+                              "by_launch_mode": res}
+        del flayers, fbatch
+
     if args.calibrate_copy:
         src = torch.randint(0, 127, (256 << 20,), dtype=torch.int8, device="cuda")
         dst = torch.empty_like(src)

@@ -48,7 +48,8 @@ typedef struct ecspmv_build_opts {
     int32_t  delta_bits;      /* width of a delta index (Section 6.2, range R_P = 2^bits): 8 (EC-CSR-8) or 4
                                  (EC-CSR-4, Section 8.2: zero fillers every 15 columns, blocks only where 64 shared
                                  columns follow one another within 15); 0 = 8 */
-    int32_t  max_granularity; /* largest block granularity g (rows per block, Section 4); 0 = 8; 1 = no extraction */
+    int32_t  max_granularity; /* largest block granularity g (rows per block, Section 4); 0 = 8 (4 for FP32 values);
+                                 1 = no extraction */
     int32_t  max_rounds;      /* cap on extraction rounds per level (Algorithm 1, inner loop); 0 = 64 */
     int32_t  num_panels;      /* row panels = workgroups of the SpMV launch; 0 = auto (256, fewer for small m) */
     int32_t  num_threads;     /* host threads for the offline phase; 0 = hardware concurrency, at most 16 */

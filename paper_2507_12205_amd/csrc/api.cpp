@@ -39,7 +39,7 @@ int map_build_error(int e)
     return ECSPMV_ERR_INVALID;
 }
 
-int parse_opts(const ecspmv_build_opts *o, ecs::BuildParams &bp)
+int parse_opts(const ecspmv_build_opts *o, ecs::BuildParams &bp, int value_bits = 16)
 {
     ecspmv_build_opts opts;
     std::memset(&opts, 0, sizeof(opts));
@@ -49,7 +49,9 @@ int parse_opts(const ecspmv_build_opts *o, ecs::BuildParams &bp)
     }
     if (opts.delta_bits != 0 && opts.delta_bits != 8 && opts.delta_bits != 4) return ECSPMV_ERR_UNSUPPORTED;
     bp.delta_bits = opts.delta_bits ? opts.delta_bits : 8;
-    const int g = opts.max_granularity ? opts.max_granularity : 8;
+    // default cap on g: 8, and 4 for FP32 values (an 8-grained FP32 unit holds 32 value registers per lane and the
+    // kernel starts to spill; larger caps can still be asked for)
+    const int g = opts.max_granularity ? opts.max_granularity : (value_bits == 32 ? 4 : 8);
     if (g != 1 && g != 2 && g != 4 && g != 8 && g != 16) return ECSPMV_ERR_UNSUPPORTED;
     bp.max_granularity = g;
     if (opts.max_rounds < 0 || opts.num_panels < 0 || opts.num_threads < 0) return ECSPMV_ERR_INVALID;
@@ -159,7 +161,7 @@ int ecspmv_build_dense_f32(const float *W, int64_t m, int64_t n, int64_t ld, con
     if (!W || !out || m <= 0 || n <= 0 || ld < n) return ECSPMV_ERR_INVALID;
     if (n > 65535 || m > 0x7fffffff) return ECSPMV_ERR_UNSUPPORTED;
     ecs::BuildParams bp;
-    int s = parse_opts(opts, bp);
+    int s = parse_opts(opts, bp, 32);
     if (s) return s;
     try {
         ecs::Csr A;
@@ -177,7 +179,7 @@ int ecspmv_build_csr_f32(const int64_t *rowptr, const int32_t *col, const float 
     if (rowptr[m] < 0 || (rowptr[m] > 0 && (!col || !val))) return ECSPMV_ERR_INVALID;
     if (n > 65535 || m > 0x7fffffff) return ECSPMV_ERR_UNSUPPORTED;
     ecs::BuildParams bp;
-    int s = parse_opts(opts, bp);
+    int s = parse_opts(opts, bp, 32);
     if (s) return s;
     try {
         ecs::Csr A;

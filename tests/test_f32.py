@@ -85,8 +85,8 @@ def test_roundtrip_bit_exact(cid, div, bits):
 def test_same_blocks_as_the_fp16_matrix_of_the_same_pattern():
     W16 = gen.make_matrix(gen.scaled(gen.config(1), 8), 0)
     W32 = make_f32(W16, 5)
-    a = E.ecspmv_build_dense(W16).ecspmv_block_sets()
-    b = E.ecspmv_build_dense_f32(W32).ecspmv_block_sets()
+    a = E.ecspmv_build_dense(W16, E.make_opts(max_granularity=4)).ecspmv_block_sets()
+    b = E.ecspmv_build_dense_f32(W32, E.make_opts(max_granularity=4)).ecspmv_block_sets()
     assert all(np.array_equal(p, q) for p, q in zip(a, b)) and len(a[0]) > 0
 
 
