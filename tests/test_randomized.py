@@ -30,7 +30,8 @@ def random_case(rng):
     x = rng.standard_normal(n).astype(np.float16)
     opts = dict(max_granularity=int(rng.choice([0, 1, 2, 4, 8, 16])),
                 num_panels=int(rng.choice([0, 1, 2, 5, 300])),
-                flags=int(rng.choice([0, 0, B.FLAG_NO_REORDER, B.FLAG_GLOBAL_MATCHING])))
+                delta_bits=int(rng.choice([0, 4, 8])),
+                flags=int(rng.choice([0, 0, B.FLAG_NO_REORDER, B.FLAG_GLOBAL_MATCHING, B.FLAG_KEEP_SMALL_SETS])))
     return W, x, opts
 
 
@@ -45,6 +46,13 @@ def test_roundtrip_random_cpu():
         assert np.array_equal(r[o], rr) and np.array_equal(c[o], cc) and np.array_equal(v[o], vv), (it, W.shape, opts)
         st = A.ecspmv_stats()
         assert sum(st.nnz_by_g) == st.nnz == len(rr)
+        if it % 3 == 0:                              # the same pattern with FP32 values
+            W32 = W.astype(np.float32) * np.float32(1.0003)
+            A32 = E.ecspmv_build_dense_f32(W32, E.make_opts(**opts))
+            r, c, v = A32.ecspmv_decode_f32()
+            rr, cc, vv = orc.pattern_triples_f32(W32)
+            o = np.lexsort((c, r))
+            assert np.array_equal(r[o], rr) and np.array_equal(c[o], cc) and np.array_equal(v[o], vv), (it, "f32")
 
 
 @pytest.mark.gpu
@@ -67,3 +75,27 @@ def test_parity_random_gpu():
         assert not np.isnan(y.astype(np.float32)).any()
         ok, ratio = orc.within_band(y, y_ref, S, 2e-3, 1e-6)
         assert ok, (it, W.shape, opts, ratio)
+        nb = int(rng.choice([0, 0, 2, 4, 8]))       # now and then: several right-hand sides, FP32 values
+        if nb and A.ecspmv_stats().nnz_by_g[3] + A.ecspmv_stats().nnz_by_g[4] == 0:
+            X = np.stack([x] + [rng.standard_normal(len(x)).astype(np.float16) for _ in range(nb - 1)], axis=1).copy()
+            Xd = torch.from_numpy(X.view(np.int16)).cuda().view(torch.float16)
+            Yd = torch.full((W.shape[0], nb), float("nan"), dtype=torch.float16, device="cuda")
+            D.run_multi(A, Xd, Yd)
+            torch.cuda.synchronize()
+            Y = Yd.cpu().numpy()
+            assert np.array_equal(np.ascontiguousarray(Y[:, 0]).view(np.uint16), y.view(np.uint16)), (it, "multi col 0")
+            for b in range(1, nb):
+                yb, Sb = orc.spmv_oracle(W, np.ascontiguousarray(X[:, b]))
+                ok, ratio = orc.within_band(Y[:, b], yb, Sb, 2e-3, 1e-6)
+                assert ok, (it, "multi", b, ratio)
+        if it % 4 == 0:
+            W32 = W.astype(np.float32) * np.float32(1.0003)
+            x32 = x.astype(np.float32)
+            A32 = E.ecspmv_build_dense_f32(W32, E.make_opts(**opts))
+            D.upload(A32)
+            y32 = torch.full((W.shape[0],), float("nan"), dtype=torch.float32, device="cuda")
+            D.run(A32, torch.from_numpy(x32).cuda(), y32)
+            torch.cuda.synchronize()
+            yr, Sr = orc.spmv_oracle_f32(W32, x32)
+            ok, ratio = orc.within_band(y32.cpu().numpy(), yr, Sr, 2e-3, 1e-6)
+            assert ok and not np.isnan(y32.cpu().numpy()).any(), (it, "f32", ratio)
