@@ -33,9 +33,6 @@ __device__ __forceinline__ float dpp_f(float old, float src)
 #define ECS_D2 2
 #define ECS_DR 1
 #endif
-#ifndef ECS_KATTR
-#define ECS_KATTR
-#endif
 #ifndef ECS_DR0B
 #define ECS_DR0B 2
 #endif
@@ -418,7 +415,7 @@ struct ResidualSet {
 // NB: right-hand sides handled at once (x holds n rows of NB values, y m rows of NB values);
 // VW: bytes per value of W, x and y (2 = FP16, 4 = FP32)
 template <int TM, int DB, bool BATCH, int K, int NB, int VW>
-__global__ __launch_bounds__(1024) ECS_KATTR void ecspmv_kernel(const ecs::EcsBatch batch)
+__global__ __launch_bounds__(1024) void ecspmv_kernel(const ecs::EcsBatch batch)
 {
     // which SpMV of the batch this workgroup works for (one item in the plain case)
     uint32_t k = 0, block0 = 0;

@@ -1,6 +1,7 @@
-"""GPU parity at the full sizes of the five workload configs, in the launch configuration bench.py times
-(default options: 256 row panels, workgroup size chosen at launch).  Every row is compared with the FP64 oracle and
-the EC-CSR image must decode to exactly W's stored entries."""
+"""GPU parity at the full sizes of the five workload configs, in the launch configurations bench.py times
+(256 row panels, workgroup size chosen at launch; EC-CSR-4, the bench's default format, and EC-CSR-8; one launch each
+and, for config 3, the whole layer in one launch).  Every row is compared with the FP64 oracle and the EC-CSR image
+must decode to exactly W's stored entries."""
 import numpy as np
 import pytest
 
@@ -12,8 +13,9 @@ pytestmark = pytest.mark.gpu
 REL, ABS = 2e-3, 1e-6
 
 
+@pytest.mark.parametrize("bits", [4, 8])
 @pytest.mark.parametrize("cid", [0, 1, 2, 3, 4])
-def test_full_size_config(cid):
+def test_full_size_config(cid, bits):
     import torch
     import paper_2507_12205_amd as E
     from paper_2507_12205_amd import device as D
@@ -21,9 +23,9 @@ def test_full_size_config(cid):
     for sid, (name, m, n) in enumerate(cfg.shapes):
         if cid == 3 and sid in (1, 2, 3, 5):
             continue                                   # same shape and recipe as q / gate
-        print(f"[case] cfg{cid} {name} {m}x{n}", flush=True)
+        print(f"[case] cfg{cid} {name} {m}x{n} EC-CSR-{bits}", flush=True)
         W, x = gen.make_case(cfg, sid)
-        A = E.ecspmv_build_dense(W)
+        A = E.ecspmv_build_dense(W, E.make_opts(delta_bits=bits))
         st = A.ecspmv_stats()
         assert st.num_panels == min(256, m // 16)
         r, c, v = A.ecspmv_decode()
@@ -43,3 +45,28 @@ def test_full_size_config(cid):
         assert np.all(err <= lim), f"{name}: worst err/lim {np.max(err / lim):.3f}"
         print(f"        worst err/lim {np.max(err / lim):.4f}  EC-CSR/CSR-32 {st.image_bytes / st.csr32_bytes:.3f}", flush=True)
         del A, xd, yd
+
+
+def test_full_size_layer_in_one_launch():
+    """Config 3 as bench.py --launch all submits it: the seven matrices of a layer, EC-CSR-4, one launch."""
+    import torch
+    import paper_2507_12205_amd as E
+    from paper_2507_12205_amd import device as D
+    cfg = gen.config(3)
+    mats, xs, ys, refs = [], [], [], []
+    for sid, (name, m, n) in enumerate(cfg.shapes):
+        print(f"[case] layer {name} {m}x{n}", flush=True)
+        W, x = gen.make_case(cfg, sid)
+        A = E.ecspmv_build_dense(W, E.make_opts(delta_bits=4))
+        D.upload(A)
+        mats.append(A)
+        xs.append(torch.from_numpy(x.view(np.int16)).cuda().view(torch.float16))
+        ys.append(torch.full((m,), float("nan"), dtype=torch.float16, device="cuda"))
+        refs.append(orc.spmv_oracle(W, x))
+    E.ecspmv_run_batch(mats, [x.data_ptr() for x in xs], [y.data_ptr() for y in ys], torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    for (name, m, n), y, (y_ref, S) in zip(cfg.shapes, ys, refs):
+        yh = y.cpu().numpy().astype(np.float64)
+        assert not np.isnan(yh).any(), name
+        err = np.abs(yh - y_ref)
+        assert np.all(err <= REL * S + ABS), f"{name}: worst err/lim {np.max(err / (REL * S + ABS)):.3f}"
