@@ -51,7 +51,8 @@ typedef struct ecspmv_build_opts {
     int32_t  max_granularity; /* largest block granularity g (rows per block, Section 4); 0 = 8 (4 for FP32 values);
                                  1 = no extraction */
     int32_t  max_rounds;      /* cap on extraction rounds per level (Algorithm 1, inner loop); 0 = 64 */
-    int32_t  num_panels;      /* row panels = workgroups of the SpMV launch; 0 = auto (256, fewer for small m) */
+    int32_t  num_panels;      /* row panels = workgroups of the SpMV launch; 0 = auto (256; fewer for small m; more
+                                 where few long rows would put more partial sums into a panel than LDS holds) */
     int32_t  num_threads;     /* host threads for the offline phase; 0 = hardware concurrency, at most 16 */
     int32_t  threads_per_wg;  /* workgroup size of the SpMV launch, multiple of 64 in [64,1024]; 0 = chosen at
                                  launch: 1024 for a lone SpMV, 512 inside a batch */

@@ -607,7 +607,16 @@ int build_image(const Csr &A, const BuildParams &bp, Image &out)
     if (n > 65535 || m > 0x7fffffff) return -2;
     const int64_t nnz = A.rowptr[(size_t)m];
     int P = bp.num_panels;
-    if (P <= 0) P = (int)std::min<int64_t>(256, std::max<int64_t>(1, m / 16));
+    if (P <= 0) {
+        P = (int)std::min<int64_t>(256, std::max<int64_t>(1, m / 16));
+        // x and one FP32 partial sum per residual lane unit (16 entries) of a panel must fit the LDS of a compute
+        // unit: where a panel of this size could not (few, long rows), more panels are made, down to one row each
+        int64_t longest = 0;
+        for (int64_t i = 0; i < m; ++i) longest = std::max(longest, A.rowptr[(size_t)i + 1] - A.rowptr[(size_t)i]);
+        const int64_t x_bytes = n * (A.value_bits / 8), budget = 150 * 1024;
+        while (P < m && x_bytes + 4 * ((nnz / P + longest) / 16 + m / P + 64) + 4096 > budget)
+            P = (int)std::min<int64_t>(m, 2 * (int64_t)P);
+    }
     if (bp.global_matching) P = 1;
     P = (int)std::min<int64_t>(P, m);
 

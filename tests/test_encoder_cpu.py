@@ -337,3 +337,16 @@ def test_panels_are_contiguous_and_cover_all_rows():
         assert hdr[0] == nxt and hdr[1] >= 1
         nxt += int(hdr[1])
     assert nxt == 1000
+
+
+def test_few_long_rows_get_more_panels_so_that_the_partial_sums_fit_lds():
+    """64 dense rows of 60000 columns: with the usual 16 rows per panel a panel would hold 60000 lane units (240 KB of
+    partial sums); the automatic choice makes more panels instead of refusing the matrix."""
+    W = np.full((64, 60000), 0.5, dtype=np.float16)
+    A = E.ecspmv_build_dense(W, E.make_opts(max_granularity=1))
+    st = A.ecspmv_stats()
+    assert st.num_panels > 4 and st.lds_bytes <= 160 * 1024
+    assert st.nnz == 64 * 60000
+    with pytest.raises(E.EcspmvError) as e:                        # an explicit panel count is taken as given
+        E.ecspmv_build_dense(W, E.make_opts(max_granularity=1, num_panels=2))
+    assert e.value.status == B.ERR_UNSUPPORTED

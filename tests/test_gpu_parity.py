@@ -327,3 +327,13 @@ def test_launches_can_be_captured_in_a_graph(E):
             assert torch.equal(e["Y"].view(torch.int16), Y.view(torch.int16)), rep
         work(torch.cuda.current_stream().cuda_stream)          # eager work between replays
         torch.cuda.synchronize()
+
+
+def test_few_long_dense_rows(E):
+    """64 dense rows of 60000 columns: the automatic panel count goes up so that the partial sums fit LDS."""
+    rng = np.random.default_rng(5)
+    W = (rng.standard_normal((64, 60000)) * 0.02).astype(np.float16)
+    x = gen.make_vector(60000, seed=6)
+    A, _ = check(E, W, x, E.make_opts(max_granularity=1), label="64 x 60000 dense")
+    assert A.ecspmv_stats().num_panels > 4
+    check(E, W, x, E.make_opts(max_granularity=1, delta_bits=4), label="64 x 60000 dense 4-bit")
