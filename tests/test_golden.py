@@ -1,0 +1,68 @@
+"""Values the paper prints for its worked examples (tests/golden/, each file cites its passage), against the oracles
+and the library.  No GPU."""
+import os
+
+import numpy as np
+
+import paper_2507_12205_amd as E
+from oracle import extraction_oracle as xo
+
+import pyformat
+
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+
+
+def lines(name):
+    with open(os.path.join(GOLDEN, name)) as f:
+        return [l.split() for l in f if l.strip() and not l.startswith("#")]
+
+
+def test_delta_example_of_section_6_2():
+    threads = []
+    for t in lines("sec6_2_delta_example.txt"):
+        base = int(t[t.index("base") + 1])
+        deltas = [int(v) for v in t[t.index("deltas") + 1:t.index("columns")]]
+        cols = [int(v) for v in t[t.index("columns") + 1:]]
+        threads.append((base, deltas, cols))
+        # the recurrence as the tests' own image reader applies it (pyformat.walk: base + cumulative sum)
+        assert (base + np.cumsum(pyformat.deltas_of(np.array(deltas, dtype=np.uint8), 8))).tolist() == cols
+        packed = np.array([deltas[0] | (deltas[1] << 4)], dtype=np.uint8)           # the same two deltas as nibbles
+        assert (base + np.cumsum(pyformat.deltas_of(packed, 4))).tolist() == cols
+    # the library stores the block's columns 2 4 5 6 (continued to a whole unit) so that they decode to the same
+    block_cols = threads[0][2] + threads[1][2] + list(range(10, 130, 2))
+    assert len(block_cols) == 64
+    W = np.zeros((2, 200), dtype=np.float16)
+    W[:, block_cols] = 1.0
+    for bits in (8, 4):
+        A = E.ecspmv_build_dense(W, E.make_opts(num_panels=1, delta_bits=bits))
+        (u,) = list(pyformat.walk(A.ecspmv_export_image()))
+        assert u["kind"] == "block" and u["g"] == 2 and u["base"] == threads[0][0]
+        assert u["cols"][:4].tolist() == threads[0][2] + threads[1][2]
+        g, rows, cols = A.ecspmv_block_sets()
+        assert cols[0][:4].tolist() == [2, 4, 5, 6]
+
+
+def test_row_split_of_section_4_3():
+    rows, blocks = {}, []
+    for t in lines("sec4_3_row_split.txt"):
+        if t[0] == "row":
+            rows[int(t[1])] = {int(v) for v in t[3:]}
+        else:
+            k = t.index("columns")
+            blocks.append((frozenset(int(v) for v in t[2:k]), tuple(int(v) for v in t[k + 1:])))
+    ids = sorted(rows)                                                  # paper rows 2, 3, 4 -> oracle rows 0, 1, 2
+    # the paper's example is drawn with blocks of four columns: the oracle's unit is a parameter
+    bs, resid = xo.hierarchical_block_extraction([set(rows[i]) for i in ids], max_granularity=2, unit=4)
+    got = sorted((frozenset(ids[m] for m in members), cols) for members, cols in bs[2])
+    assert got == sorted(blocks)
+    assert resid == [[], [], []]
+    assert xo.row_matching([xo.LevelRow(set(rows[i]), (k,)) for k, i in enumerate(ids)], unit=4) == [(2, 0)]   # round 1
+    # the library (unit = 64 columns): the same example with every paper column widened to 16 columns
+    wide = lambda cs: sorted(16 * c + k for c in cs for k in range(16))
+    W = np.zeros((3, 16 * 9), dtype=np.float16)
+    for k, i in enumerate(ids):
+        W[k, wide(rows[i])] = 1.0
+    A = E.ecspmv_build_dense(W, E.make_opts(num_panels=1, max_granularity=2))
+    g, brow, bcol = A.ecspmv_block_sets()
+    lib = sorted((frozenset(ids[r] for r in brow[2 * u:2 * u + 2]), tuple(bcol[u].tolist())) for u in range(len(g)))
+    assert lib == sorted((rs, tuple(wide(cs))) for rs, cs in blocks)
