@@ -3,9 +3,14 @@
 //
 // One workgroup per row panel.  The workgroup stages x and the panel's tables in LDS once, then its
 // wavefronts stream the panel's delta and value arrays with 128-bit loads, rebuild absolute columns with
-// cross-lane prefix scans (DPP), gather x from LDS, accumulate in FP32, reduce across lanes, and leave one
-// FP32 partial per (unit, row) in an LDS slot.  After a barrier the slots of each row are added in a fixed
-// order and the row is stored as FP16.  No atomics, no pre-zeroed y, bit-reproducible results.
+// cross-lane prefix scans (DPP), gather x from LDS and accumulate in FP32.  A block unit reduces its 16 lanes and
+// leaves one FP32 partial per (unit, row) in an LDS slot; a residual lane unit (16 entries of one row) leaves its
+// own partial sum.  After a barrier the slots and partial sums of each row are added in a fixed order and the
+// row is stored.  No atomics, no pre-zeroed y, bit-reproducible results.
+//
+// One kernel template covers the variants: which block sets the image holds (TM), 8- or 4-bit deltas (DB),
+// buffer depths for launches that carry several SpMVs (BATCH), loads per thread of the staging phase (K),
+// 1, 2, 4 or 8 right-hand sides (NB), FP16 or FP32 values (VW).
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
 #include <stdint.h>
