@@ -244,14 +244,17 @@ struct BlockSet {
     {
         return 4u * (c0 + i * c.nwaves) + (c.lane >> 4);
     }
-    __device__ __forceinline__ void prologue(const Ctx &c, const uint32_t *hdr, int t)
+    // `dealt`: chunks of the sets handled before this one.  The chunks of all sets are dealt to the wavefronts as one
+    // round-robin sequence, so that the odd chunks of different sets go to different wavefronts.
+    __device__ __forceinline__ void prologue(const Ctx &c, const uint32_t *hdr, int t, uint32_t &dealt)
     {
         nu = hdr[PH_NUNITS + t];
         bd_off = hdr[PH_BD_OFF + t];
         bv_off = hdr[PH_BV_OFF + t];
         utab = reinterpret_cast<const uint16_t *>(c.meta + hdr[PH_UTAB_OFF + t]);
         const uint32_t nch = (nu + 3u) >> 2;
-        c0 = c.wave;
+        c0 = (c.wave + c.nwaves - dealt % c.nwaves) % c.nwaves;
+        dealt += nch;
         n = nch > c0 ? (nch - c0 + c.nwaves - 1u) / c.nwaves : 0u;
         // Every buffer is requested whether or not this wavefront has that many chunks (a missing chunk reads the
         // panel header instead): every wavefront then enters the loop below with the same loads in flight, which
@@ -371,7 +374,7 @@ struct ResidualSet {
     float *part;
 
     __device__ __forceinline__ uint32_t chunk_of(const Ctx &c, uint32_t i) const { return c0 + i * c.nwaves; }
-    __device__ __forceinline__ void prologue(const Ctx &c, const uint32_t *hdr)
+    __device__ __forceinline__ void prologue(const Ctx &c, const uint32_t *hdr, uint32_t dealt)
     {
         nlanes = hdr[PH_NRLANES];
         rd_off = hdr[PH_RD_OFF];
@@ -381,7 +384,7 @@ struct ResidualSet {
         rch = reinterpret_cast<const EcsRChunk *>(c.meta + hdr[PH_RCHUNK_OFF]);
         ren = reinterpret_cast<const EcsREntry *>(c.meta + hdr[PH_RENTRY_OFF]);
         const uint32_t nch = (nlanes + 63u) >> 6;
-        c0 = c.wave;
+        c0 = (c.wave + c.nwaves - dealt % c.nwaves) % c.nwaves;
         n = nch > c0 ? (nch - c0 + c.nwaves - 1u) / c.nwaves : 0u;
         // unconditional, like the block sets: a missing chunk reads the panel header
 #pragma unroll
@@ -493,11 +496,12 @@ __global__ __launch_bounds__(1024) void ecspmv_kernel(const ecs::EcsBatch batch)
     BlockSet<4, DB, wide ? 1 : D4, NB, VW> b4;
     BlockSet<2, DB, wide ? 2 : D2, NB, VW> b2;
     ResidualSet<DB, wide ? 2 : (TM == 0 && BATCH ? DR0B : DR), BATCH, NB, VW> rs;
-    if constexpr ((TM & 8) != 0) b16.prologue(c, hdr, 3);
-    if constexpr ((TM & 4) != 0) b8.prologue(c, hdr, 2);
-    if constexpr ((TM & 2) != 0) b4.prologue(c, hdr, 1);
-    if constexpr ((TM & 1) != 0) b2.prologue(c, hdr, 0);
-    rs.prologue(c, hdr);
+    uint32_t dealt = 0;
+    if constexpr ((TM & 8) != 0) b16.prologue(c, hdr, 3, dealt);
+    if constexpr ((TM & 4) != 0) b8.prologue(c, hdr, 2, dealt);
+    if constexpr ((TM & 2) != 0) b4.prologue(c, hdr, 1, dealt);
+    if constexpr ((TM & 1) != 0) b2.prologue(c, hdr, 0, dealt);
+    rs.prologue(c, hdr, dealt);
 
     // tables and x into LDS
     uint4 *meta4 = reinterpret_cast<uint4 *>(meta);
