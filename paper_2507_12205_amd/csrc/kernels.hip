@@ -450,7 +450,7 @@ __global__ __launch_bounds__(1024) void ecspmv_kernel(const ecs::EcsBatch batch)
     c.xs = xs;
     c.meta = meta;
     c.slots = slots;
-    c.wave = tid >> 6;
+    c.wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(tid >> 6));      // wave-uniform: scalar arithmetic on it
     c.lane = tid & 63;
     c.nwaves = nt >> 6;
 
