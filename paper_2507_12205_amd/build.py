@@ -27,6 +27,8 @@ def build(verbose: bool = False, extra_flags=(), out: str = LIB) -> str:
     """Compile every source for gfx950 and link the shared library.  Needs hipcc; no GPU required."""
     cmd = ["hipcc", "-O3", "-std=c++17", "-fPIC", "-shared", "--offload-arch=gfx950",
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           # the first kernel arguments (count, workgroup size, first item of a launch) arrive in registers
+           "-mllvm", "-amdgpu-kernarg-preload-count=16",
            "-mpopcnt", "-pthread", "-Wall", "-Wno-unused-function",
            "-x", "hip"]
     cmd += list(extra_flags)

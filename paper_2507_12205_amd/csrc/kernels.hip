@@ -423,15 +423,28 @@ struct ResidualSet {
 // NB: right-hand sides handled at once (x holds n rows of NB values, y m rows of NB values);
 // VW: bytes per value of W, x and y (2 = FP16, 4 = FP32)
 template <int TM, int DB, bool BATCH, int K, int NB, int VW>
-__global__ __launch_bounds__(1024) void ecspmv_kernel(const ecs::EcsBatch batch)
+__global__ __launch_bounds__(1024) void ecspmv_kernel(const uint32_t count, const uint32_t threads, const uint8_t *image0,
+                                                      const uint16_t *x0, uint16_t *y0, const uint32_t n0,
+                                                      const uint32_t panel_stride0, const uint32_t meta_stride0,
+                                                      const uint32_t x_bytes0, const uint32_t block_end0,
+                                                      const ecs::EcsBatch batch)
 {
     // which SpMV of the batch this workgroup works for (one item in the plain case)
-    uint32_t k = 0, block0 = 0;
-    while (k + 1 < batch.count && blockIdx.x >= batch.item[k].block_end) {
-        block0 = batch.item[k].block_end;
-        ++k;
+    // What a lone launch needs (count, workgroup size, the first item) comes first in the kernel arguments, as
+    // plain values the hardware can hand over in registers; the table behind them is read only by launches that
+    // carry several SpMVs.
+    ecs::EcsBatchItem it;
+    it.image = image0, it.x = x0, it.y = y0, it.n = n0, it.panel_stride = panel_stride0, it.meta_stride = meta_stride0;
+    it.x_bytes = x_bytes0, it.block_end = block_end0, it.pad_ = 0;
+    uint32_t block0 = 0;
+    if (count > 1) {
+        uint32_t k = 0;
+        while (k + 1 < count && blockIdx.x >= batch.item[k].block_end) {
+            block0 = batch.item[k].block_end;
+            ++k;
+        }
+        if (k) it = batch.item[k];
     }
-    const ecs::EcsBatchItem &it = batch.item[k];
     const uint16_t *__restrict__ x = it.x;
     uint16_t *__restrict__ y = it.y;
     const uint32_t n = it.n * NB * (VW / 2), meta_stride = it.meta_stride, x_bytes = it.x_bytes;   // n: 2-byte units of x
@@ -442,7 +455,7 @@ __global__ __launch_bounds__(1024) void ecspmv_kernel(const ecs::EcsBatch batch)
     uint8_t *meta = lds + x_bytes;
     float *slots = reinterpret_cast<float *>(lds + x_bytes + meta_stride);
 
-    const uint32_t tid = threadIdx.x, nt = blockDim.x;
+    const uint32_t tid = threadIdx.x, nt = threads;
     const uint8_t *panel = it.image + ECS_IMAGE_HEADER + (size_t)it.panel_stride * (blockIdx.x - block0);
 
     Ctx c;
@@ -473,7 +486,7 @@ __global__ __launch_bounds__(1024) void ecspmv_kernel(const ecs::EcsBatch batch)
     // was measured: in a lone launch all of them repeat the last piece (one cache line, few such threads); with
     // several SpMVs in the launch there are many such threads (K follows the widest x) and they wrap around, so
     // that the lanes of a wavefront write to different LDS addresses.
-    const bool wrap = batch.count > 1;
+    const bool wrap = count > 1;
     auto piece_index = [&](uint32_t k) -> uint32_t {
         const uint32_t idx = tid + k * nt;
         return idx < ntot ? idx : (wrap ? idx % ntot : ntot - 1u);
@@ -621,7 +634,9 @@ static int launch_k(const EcsBatch &batch, uint32_t threads, uint32_t lds_bytes,
         attr_set_for = lds_bytes;
     }
     const uint32_t grid = batch.item[batch.count - 1].block_end;
-    hipLaunchKernelGGL((ecspmv_kernel<TM, DB, BATCH, K, NB, VW>), dim3(grid), dim3(threads), lds_bytes, (hipStream_t)stream, batch);
+    hipLaunchKernelGGL((ecspmv_kernel<TM, DB, BATCH, K, NB, VW>), dim3(grid), dim3(threads), lds_bytes, (hipStream_t)stream,
+                       batch.count, threads, batch.item[0].image, batch.item[0].x, batch.item[0].y, batch.item[0].n,
+                       batch.item[0].panel_stride, batch.item[0].meta_stride, batch.item[0].x_bytes, batch.item[0].block_end, batch);
     return (int)hipGetLastError();
 }
 
