@@ -323,6 +323,23 @@ def main():
             torch.cuda.synchronize()
             ms = ev0.elapsed_time(ev1)
             out.setdefault("stream_read_ceiling_gbps", {})[f"{nwg}wg"] = round(tot / (ms * 1e-3) / 1e9, 1)
+        # ... and in one launch per step: buffers of one step's bytes each, rotated the same way
+        step_bytes = sum(int(e["st"].image_bytes) for e in mats[0]) // 16 * 16
+        big = [torch.randint(0, 255, (step_bytes,), dtype=torch.uint8, device="cuda") for _ in range(copies)]
+        chk4 = torch.zeros(4096, dtype=torch.int32, device="cuda")
+        for nwg in (512, 4096):
+            for s in range(2 * copies):
+                E.ecspmv_stream_read(big[s % copies].data_ptr(), step_bytes, chk4.data_ptr(), nwg, sh)
+            torch.cuda.synchronize()
+            ev0.record(stream)
+            reps = min(args.steps, 8 * copies)
+            for s in range(reps):
+                E.ecspmv_stream_read(big[s % copies].data_ptr(), step_bytes, chk4.data_ptr(), nwg, sh)
+            ev1.record(stream)
+            torch.cuda.synchronize()
+            out["stream_read_ceiling_gbps"][f"one_launch_per_step_{nwg}wg"] = round(
+                step_bytes * reps / (ev0.elapsed_time(ev1) * 1e-3) / 1e9, 1)
+        del big
 
         # plain CSR kernel on the same matrices (first two copies, rotation > 512 MB of CSR data)
         csr_layers = []

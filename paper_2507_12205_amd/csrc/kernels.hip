@@ -42,11 +42,10 @@ __device__ __forceinline__ float dpp_f(float old, float src)
 #define ECS_DR0B 2
 #endif
 // Register buffers per set (4-, 2- and 1-grained).  Measured on the box: one buffer for the 4-grained and residual
-// sets and two for the 2-grained set keep the kernel at 72 VGPRs, so three 512-thread workgroups share a compute
-// unit; deeper buffering costs that third workgroup and is slower.  An image with no blocks at all (only the
-// residual set) leaves room for two residual buffers at under 64 VGPRs: faster inside a batch, where many
-// wavefronts share a compute unit and each must keep more bytes on the way, slower for a lone launch, whose
-// wavefronts have one or two chunks each.
+// sets and two for the 2-grained set; deeper buffering takes the kernel past the next step in registers (fewer
+// wavefronts per SIMD) and is slower.  An image with no blocks at all (only the residual set) leaves room for two
+// residual buffers at under 64 VGPRs: faster inside a batch, where many wavefronts share a compute unit and each
+// must keep more bytes on the way, slower for a lone launch, whose wavefronts have one or two chunks each.
 constexpr int D4 = ECS_D4, D2 = ECS_D2, DR = ECS_DR, DR0B = ECS_DR0B;
 
 constexpr int DPP_ROW_SHR1 = 0x111, DPP_ROW_SHR2 = 0x112, DPP_ROW_SHR4 = 0x114, DPP_ROW_SHR8 = 0x118;
@@ -500,8 +499,8 @@ __global__ __launch_bounds__(1024) void ecspmv_kernel(const uint32_t count, cons
     if constexpr (K > 2) s2 = *piece(2), s3 = *piece(3);
     __builtin_amdgcn_sched_barrier(0);      // these loads do not wait for the header: keep them ahead of those that do
 
-    // As soon as the header is here, the first two chunks of every set are requested, before anything is computed
-    // and before the tables and x have even reached LDS.
+    // As soon as the header is here, the first chunks of every set are requested (one per register buffer), before
+    // anything is computed and before the tables and x have even reached LDS.
     // buffers per set: deeper where chunks are small and frequent, shallower where registers run out
     constexpr bool wide = (TM & 12) != 0;
     BlockSet<16, DB, 1, NB, VW> b16;
@@ -593,18 +592,21 @@ __global__ __launch_bounds__(256) void csr_kernel(const int32_t *__restrict__ ro
     if (lane == 0) y[row] = __half_as_ushort(__float2half_rn(acc));
 }
 
-// ---- streaming read: every byte once, 128-bit loads, grid-stride, four loads in flight per lane
+// ---- streaming read: every byte once, non-temporal 128-bit loads as in the product kernel, grid-stride, four
+// loads in flight per lane
 __global__ __launch_bounds__(1024) void stream_read_kernel(const uint4 *__restrict__ buf, uint64_t nvec, uint32_t *__restrict__ out)
 {
     const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
     uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
     uint32_t acc = 0;
+    const uint8_t *bytes = reinterpret_cast<const uint8_t *>(buf);
     for (; i + 3 * stride < nvec; i += 4 * stride) {
-        const uint4 a = buf[i], b = buf[i + stride], c = buf[i + 2 * stride], d = buf[i + 3 * stride];
+        const uint4 a = load16(bytes + 16 * i), b = load16(bytes + 16 * (i + stride)), c = load16(bytes + 16 * (i + 2 * stride)),
+                    d = load16(bytes + 16 * (i + 3 * stride));
         acc ^= a.x ^ a.y ^ a.z ^ a.w ^ b.x ^ b.y ^ b.z ^ b.w ^ c.x ^ c.y ^ c.z ^ c.w ^ d.x ^ d.y ^ d.z ^ d.w;
     }
     for (; i < nvec; i += stride) {
-        const uint4 a = buf[i];
+        const uint4 a = load16(bytes + 16 * i);
         acc ^= a.x ^ a.y ^ a.z ^ a.w;
     }
     __shared__ uint32_t red[16];
