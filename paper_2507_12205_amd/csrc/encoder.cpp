@@ -671,6 +671,7 @@ int build_image(const Csr &A, const BuildParams &bp, Image &out)
     uint32_t stride = 256, meta = 16, slots = 1;
     for (auto &im : imgs) {
         if (im.err) return im.err;
+        if (im.bytes.size() > 0xFFFFF000ull) return -2;                      // offsets inside a panel are 32-bit
         stride = std::max<uint32_t>(stride, (uint32_t)im.bytes.size());
         meta = std::max(meta, im.meta_bytes);
         slots = std::max(slots, im.lds_slots);
