@@ -55,6 +55,7 @@ def parse_args():
                          "the kernel statistics cover exactly the launches the bench times)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip hot-cache, CSR and streaming-read legs")
+    ap.add_argument("--no-other-configs", action="store_true", help="skip the runs of the other workload configs")
     ap.add_argument("--detail", type=str, default="", help="write per-shape details to this JSON file")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device-to-device copy three times (known traffic, for scaling "
@@ -95,7 +96,7 @@ def main():
 
     # ---- build the rotation set -------------------------------------------------------------------------
     t_prep = time.time()
-    est_layer_bytes = sum(2.9 * cfg.density * m * n for _, m, n in cfg.shapes)
+    est_layer_bytes = sum(2.5 * cfg.density * m * n for _, m, n in cfg.shapes)     # a lower bound: the set is never short
     copies = args.copies or max(2, int(np.ceil(max(cfg.rotation_bytes, 1) * 1.05 / est_layer_bytes)))
     mats = []      # [copy][shape] -> dict
 
@@ -522,6 +523,25 @@ def main():
                                   [int(sum(e["st"].nnz_by_g[k] for e in flayers[0])) for k in range(5)],
                               "by_launch_mode": res}
         del flayers, fbatch
+
+    if not args.no_extras and not args.no_other_configs:
+        # the other workload configs under the same protocol (own cold rotation, the same three launch modes), each
+        # in a child process that runs this file with --config
+        import subprocess
+        others = {}
+        for cid in [c for c in (1, 2, 3, 4) if c != args.config]:
+            cmd = [sys.executable, os.path.abspath(__file__), "--config", str(cid), "--no-extras", "--no-cpu-baseline",
+                   "--delta-bits", str(args.delta_bits), "--steps", str(args.steps), "--warmup", str(args.warmup)]
+            r = subprocess.run(cmd, capture_output=True, text=True, timeout=900)
+            if r.returncode != 0 or not r.stdout.strip():
+                others[str(cid)] = {"error": r.stderr[-300:]}
+                continue
+            d = json.loads(r.stdout.strip().splitlines()[-1])
+            others[str(cid)] = {"workload": d["config"]["workload"], "bytes_per_nnz": d["storage"]["bytes_per_nnz"],
+                                "eccsr_over_csr32": d["storage"]["eccsr_over_csr32"],
+                                "nnz_by_granularity_1_2_4_8_16": d["storage"]["nnz_by_granularity_1_2_4_8_16"],
+                                "by_launch_mode": d["by_launch_mode"]}
+        out["other_configs"] = others
 
     if args.calibrate_copy:
         src = torch.randint(0, 127, (256 << 20,), dtype=torch.int8, device="cuda")
