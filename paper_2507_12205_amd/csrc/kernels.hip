@@ -417,7 +417,8 @@ struct ResidualSet {
 };
 
 // TM: bit t set = the image holds units of granularity 2 << t somewhere (the residual set is always handled);
-// DB: width of the delta indices in bits; BATCH: buffer depths for a launch that carries several SpMVs;
+// DB: width of the delta indices in bits; BATCH: the variant for a launch that carries several SpMVs (residual-only
+// images: deeper buffers; one block set: everything requested before the first barrier);
 // K: 16-byte pieces of [tables | x] each thread brings to LDS before the generic loop takes the rest;
 // NB: right-hand sides handled at once (x holds n rows of NB values, y m rows of NB values);
 // VW: bytes per value of W, x and y (2 = FP16, 4 = FP32)
@@ -507,13 +508,18 @@ __global__ __launch_bounds__(1024) void ecspmv_kernel(const uint32_t count, cons
     BlockSet<8, DB, 1, NB, VW> b8;
     BlockSet<4, DB, wide ? 1 : D4, NB, VW> b4;
     BlockSet<2, DB, wide ? 2 : D2, NB, VW> b2;
-    ResidualSet<DB, wide ? 2 : (TM == 0 && BATCH ? DR0B : DR), BATCH, NB, VW> rs;
+    ResidualSet<DB, wide ? 2 : (TM == 0 && BATCH ? DR0B : DR), TM == 0 && BATCH, NB, VW> rs;
+    // A lone launch of an image with one block set requests the residual set's first chunks only after the barrier:
+    // a wavefront cannot pass the barrier before its requests are out, and with both sets requested up front the
+    // whole panel is on its way before anything is computed (measured: 3-5 % of a lone launch; with more sets, or
+    // with other workgroups sharing the compute unit, requesting everything first is the faster order).
+    constexpr bool residual_late = TM == 1 && !BATCH && NB == 1 && VW == 2;
     uint32_t dealt = 0;
     if constexpr ((TM & 8) != 0) b16.prologue(c, hdr, 3, dealt);
     if constexpr ((TM & 4) != 0) b8.prologue(c, hdr, 2, dealt);
     if constexpr ((TM & 2) != 0) b4.prologue(c, hdr, 1, dealt);
     if constexpr ((TM & 1) != 0) b2.prologue(c, hdr, 0, dealt);
-    rs.prologue(c, hdr, dealt);
+    if constexpr (!residual_late) rs.prologue(c, hdr, dealt);
 
     // tables and x into LDS
     uint4 *meta4 = reinterpret_cast<uint4 *>(meta);
@@ -536,6 +542,7 @@ __global__ __launch_bounds__(1024) void ecspmv_kernel(const uint32_t count, cons
     for (uint32_t i = (x_fast ? nvec * 8u : 0u) + tid; i < n; i += nt) xs[i] = x[i];
     __syncthreads();
 
+    if constexpr (residual_late) rs.prologue(c, hdr, dealt);
     if constexpr ((TM & 8) != 0) b16.run(c);
     if constexpr ((TM & 4) != 0) b8.run(c);
     if constexpr ((TM & 2) != 0) b4.run(c);
@@ -667,10 +674,13 @@ static int launch_tm(const EcsBatch &batch, uint32_t threads, uint32_t lds_bytes
     if (value_bits == 32)
         return delta_bits == 4 ? launch_k<TM, 4, false, 4, 1, 4>(batch, threads, lds_bytes, stream)
                                : launch_k<TM, 8, false, 4, 1, 4>(batch, threads, lds_bytes, stream);
-    // only the residual-only kernel has a second set of buffer depths
-    if (TM == 0 && batch.count > 1)
-        return delta_bits == 4 ? launch_b<TM, 4, TM == 0>(batch, threads, lds_bytes, stream)
-                               : launch_b<TM, 8, TM == 0>(batch, threads, lds_bytes, stream);
+    // Residual-only images and images with one block set have a second variant for launches that carry several
+    // SpMVs.  The residual-only one (deeper buffers) pays once more than two 512-thread workgroups share a compute
+    // unit; up to that a compute unit holds as many wavefronts as in a lone launch.
+    const uint32_t grid = batch.item[batch.count - 1].block_end;
+    if ((TM == 0 && batch.count > 1 && grid > 512) || (TM == 1 && batch.count > 1))
+        return delta_bits == 4 ? launch_b<TM, 4, TM <= 1>(batch, threads, lds_bytes, stream)
+                               : launch_b<TM, 8, TM <= 1>(batch, threads, lds_bytes, stream);
     return delta_bits == 4 ? launch_b<TM, 4, false>(batch, threads, lds_bytes, stream)
                            : launch_b<TM, 8, false>(batch, threads, lds_bytes, stream);
 }
