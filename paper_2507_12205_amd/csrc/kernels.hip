@@ -675,10 +675,10 @@ static int launch_tm(const EcsBatch &batch, uint32_t threads, uint32_t lds_bytes
         return delta_bits == 4 ? launch_k<TM, 4, false, 4, 1, 4>(batch, threads, lds_bytes, stream)
                                : launch_k<TM, 8, false, 4, 1, 4>(batch, threads, lds_bytes, stream);
     // Residual-only images and images with one block set have a second variant for launches that carry several
-    // SpMVs.  The residual-only one (deeper buffers) pays once more than two 512-thread workgroups share a compute
-    // unit; up to that a compute unit holds as many wavefronts as in a lone launch.
+    // SpMVs.  The residual-only one (deeper buffers) pays once more than three 512-thread workgroups per compute
+    // unit are launched (measured at 2, 3 and 7 per compute unit: slower, 1 % slower, faster).
     const uint32_t grid = batch.item[batch.count - 1].block_end;
-    if ((TM == 0 && batch.count > 1 && grid > 512) || (TM == 1 && batch.count > 1))
+    if ((TM == 0 && batch.count > 1 && grid > 768) || (TM == 1 && batch.count > 1))
         return delta_bits == 4 ? launch_b<TM, 4, TM <= 1>(batch, threads, lds_bytes, stream)
                                : launch_b<TM, 8, TM <= 1>(batch, threads, lds_bytes, stream);
     return delta_bits == 4 ? launch_b<TM, 4, false>(batch, threads, lds_bytes, stream)
