@@ -146,7 +146,10 @@ class Matrix:
         self.d_image = None          # whatever object owns the device buffer (kept alive here)
 
     def __del__(self):
-        self.destroy()
+        try:
+            self.destroy()
+        except Exception:       # interpreter shutdown: the module's globals may be gone already
+            pass
 
     def destroy(self):
         if getattr(self, "_h", None) is not None and self._h.value:
@@ -286,9 +289,12 @@ class CsrMatrix:
         self.d_buf = None
 
     def __del__(self):
-        if getattr(self, "_h", None) is not None and self._h.value:
-            lib().ecspmv_csr_destroy(self._h)
-            self._h = c_void_p(0)
+        try:
+            if getattr(self, "_h", None) is not None and self._h.value:
+                lib().ecspmv_csr_destroy(self._h)
+                self._h = c_void_p(0)
+        except Exception:       # interpreter shutdown: the module's globals may be gone already
+            pass
 
     def ecspmv_csr_device_bytes(self) -> int:
         b = c_size_t(0)
