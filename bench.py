@@ -291,6 +291,22 @@ def main():
                "achieved": a["gbps"], "frac": round(a["gbps"] / HBM_PEAK_GBPS, 4)} for mode, a in alt.items()}
 
     if not args.no_extras:
+        # spread over the rotation: every step of the chosen launch mode bracketed by its own pair of events (the
+        # events add to each step, so these sit above the aggregate figure)
+        nst = min(args.steps, 100)
+        evs = [torch.cuda.Event(enable_timing=True) for _ in range(nst + 1)]
+        for s in range(copies):
+            run_layer(mats[s % copies])
+        torch.cuda.synchronize()
+        evs[0].record(stream)
+        for s in range(nst):
+            run_layer(mats[s % copies])
+            evs[s + 1].record(stream)
+        torch.cuda.synchronize()
+        per = sorted(evs[s].elapsed_time(evs[s + 1]) * 1e3 for s in range(nst))
+        out["per_step_us"] = {"launch_mode": args.launch, "steps": nst, "min": round(per[0], 3),
+                              "median": round(per[nst // 2], 3), "max": round(per[-1], 3)}
+
         # hot cache: the same layer over and over (working set of one layer still exceeds L2)
         for _ in range(3):
             run_layer(mats[0])
