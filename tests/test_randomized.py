@@ -75,6 +75,13 @@ def test_parity_random_gpu():
         assert not np.isnan(y.astype(np.float32)).any()
         ok, ratio = orc.within_band(y, y_ref, S, 2e-3, 1e-6)
         assert ok, (it, W.shape, opts, ratio)
+        if it % 2 == 0:                             # the same matrix three times in one launch: the same bits
+            ys = [torch.full((W.shape[0],), float("nan"), dtype=torch.float16, device="cuda") for _ in range(3)]
+            E.Batch([A, A, A], [xd.data_ptr()] * 3, [t.data_ptr() for t in ys]).ecspmv_run_batch(
+                torch.cuda.current_stream().cuda_stream)
+            torch.cuda.synchronize()
+            for t in ys:
+                assert np.array_equal(t.cpu().numpy().view(np.uint16), y.view(np.uint16)), (it, "batch of three")
         nb = int(rng.choice([0, 0, 2, 4, 8]))       # now and then: several right-hand sides, FP32 values
         if nb and A.ecspmv_stats().nnz_by_g[3] + A.ecspmv_stats().nnz_by_g[4] == 0:
             X = np.stack([x] + [rng.standard_normal(len(x)).astype(np.float16) for _ in range(nb - 1)], axis=1).copy()
