@@ -3,7 +3,8 @@
  *
  * EC-CSR (paper, Section 6) stores a pruned FP16 weight matrix as dense g-grained blocks
  * found by hierarchical block extraction (Section 4, Algorithms 1 and 2) plus the
- * residual 1-grained rows, with 8-bit delta-encoded column indices (Section 6.2).
+ * residual 1-grained rows, with 8-bit or 4-bit delta-encoded column indices (Section 6.2; EC-CSR-8 and
+ * EC-CSR-4 of Section 8.2).
  * ecspmv_build_* runs the offline phase on the host (Sections 4, 5, 6); ecspmv_run is the
  * online phase (Section 7): one HIP kernel launch on a caller-supplied stream.
  *
@@ -71,16 +72,16 @@ typedef struct ecspmv_stats_t {
     uint32_t struct_size;
     int64_t  m, n, nnz;                /* stored entries of W */
     int64_t  image_bytes;              /* whole device image */
-    int64_t  value_bytes;              /* FP16 values incl. padding */
-    int64_t  delta_bytes;              /* 8-bit delta indices incl. padding */
+    int64_t  value_bytes;              /* values (FP16, or FP32 for an _f32 build) incl. padding */
+    int64_t  delta_bytes;              /* delta indices (one or half a byte each) incl. padding */
     int64_t  meta_bytes;               /* headers, bases, row/slot tables */
     int64_t  slack_bytes;              /* alignment gaps and per-panel slack up to the common panel stride */
-    int64_t  csr32_bytes;              /* 6*nnz + 4*(m+1): int32 columns + FP16 values + int32 row pointers */
-    int64_t  csr16_bytes;              /* 4*nnz + 4*(m+1) */
+    int64_t  csr32_bytes;              /* 6*nnz + 4*(m+1): int32 columns + FP16 values + int32 row pointers (8*nnz with FP32 values) */
+    int64_t  csr16_bytes;              /* 4*nnz + 4*(m+1): the same with int16 columns (6*nnz with FP32 values) */
     int64_t  nnz_by_g[5];              /* stored entries held at granularity 1, 2, 4, 8, 16 */
     int64_t  units_by_g[5];            /* [0] = residual lane units (16 elements), [t>=1] = 64-column units of g = 2^t */
     int64_t  pad_elements;             /* explicit zeros: gap fillers + row-tail alignment (residual rows only) */
-    int64_t  gap_pad_elements;         /* of those, zeros inserted because a column gap exceeded 255 */
+    int64_t  gap_pad_elements;         /* of those, zeros inserted because a column gap exceeded the largest delta (255 or 15) */
     int32_t  num_panels, threads_per_wg;
     int64_t  panel_stride, meta_stride, lds_bytes;
     int64_t  max_panel_bytes, min_panel_bytes;
@@ -153,9 +154,9 @@ int ecspmv_run(const ecspmv_matrix *A, const void *d_x, void *d_y, void *stream)
 /* The same for `count` independent SpMVs in one kernel launch per 16 matrices (a launch also ends where the
  * delta width or the value width changes from one matrix to the next): y_i = W_i x_i.  As, d_xs, d_ys:
  * host arrays of `count` handles / device pointers.  The SpMVs must not depend on one another (no y_i may be an
- * x_j of the same call).  Meant for the
- * projections of a decoder layer that share a launch: workgroups of the next matrix start while the last ones of
- * the previous matrix drain, which removes the launch and ramp-up cost between small SpMVs. */
+ * x_j of the same call).  Meant for the projections of a decoder layer that do not depend on one another:
+ * workgroups of the next matrix start while the last ones of the previous matrix drain, which removes the launch
+ * and ramp-up cost between small SpMVs.  Every y_i has the bits a lone ecspmv_run would give. */
 int ecspmv_run_batch(const ecspmv_matrix *const *As, const void *const *d_xs, void *const *d_ys, int32_t count,
                      void *stream);
 
@@ -164,8 +165,8 @@ int ecspmv_run_batch(const ecspmv_matrix *const *As, const void *const *d_xs, vo
  * FP16 (row-major: the nb values that belong to one column of W are adjacent), d_Y: device, m rows of nb FP16; every
  * entry of Y is written.  The deltas are decoded once and every stored entry of W is read once for all nb products.
  * One kernel launch, asynchronous on `stream`, no allocation.  nb = 1 is ecspmv_run.
- * ECSPMV_ERR_UNSUPPORTED for FP32 matrices, if the image holds 8- or 16-grained block sets (build with max_granularity <= 4 for this
- * call) or if 2*n*nb bytes of X plus 4*nb bytes per partial sum do not fit the LDS of a compute unit;
+ * ECSPMV_ERR_UNSUPPORTED for FP32 matrices, if the image holds 8- or 16-grained block sets (build with
+ * max_granularity <= 4 for this call) or if 2*n*nb bytes of X plus 4*nb bytes per partial sum do not fit the LDS of a compute unit;
  * ECSPMV_ERR_INVALID for other nb. */
 int ecspmv_run_multi(const ecspmv_matrix *A, const void *d_X, void *d_Y, int32_t nb, void *stream);
 
