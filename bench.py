@@ -12,6 +12,10 @@ as the workload is stated; `groups` / `all` = the batched entry point (one launc
 independent in a decoder layer / one launch for all seven).  All three are always measured and reported in
 `by_launch_mode`; `value` and `roofline` are those of the mode given by `--launch`.
 
+Beside the headline figures the default run adds, as further keys of the same line: the spread of the step times
+(`per_step_us`), one matrix hot in cache, the plain-read ceiling, the plain CSR kernel, the other delta width, several
+right-hand sides, FP32 values, and the other workload configs (`other_configs`, each in a child process).
+
 Prints ONE JSON line: whole-job effective HBM GB/s (bytes that must be read or written per SpMV: EC-CSR values,
 deltas and tables + x + y, divided by time), microseconds per SpMV, the roofline of the SpMV kernel and the CPU
 oracle's rate on the host cores as a baseline.
