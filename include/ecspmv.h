@@ -103,7 +103,7 @@ int ecspmv_build_dense(const uint16_t *W, int64_t m, int64_t n, int64_t ld,
 int ecspmv_build_csr(const int64_t *rowptr, const int32_t *col, const uint16_t *val,
                      int64_t m, int64_t n, const ecspmv_build_opts *opts, ecspmv_matrix **out);
 
-/* The same for FP32 values (the paper's other precision, Sections 3 and 8): W, and later x and y of ecspmv_run, are
+/* The same for FP32 values (the paper's other precision: its evaluation, Sections 8.1 and 8.2, covers FP32 and FP16): W, and later x and y of ecspmv_run, are
  * float.  An entry is stored iff it is neither +0 nor -0.  The image keeps 4-byte values; everything else (block
  * extraction, delta indices, layout) is unchanged.  csr32_bytes / csr16_bytes of the stats then count 4-byte values. */
 int ecspmv_build_dense_f32(const float *W, int64_t m, int64_t n, int64_t ld,
@@ -160,7 +160,7 @@ int ecspmv_run(const ecspmv_matrix *A, const void *d_x, void *d_y, void *stream)
 int ecspmv_run_batch(const ecspmv_matrix *const *As, const void *const *d_xs, void *const *d_ys, int32_t count,
                      void *stream);
 
-/* Y = W X for nb right-hand sides at once (the paper's problem statement, Section 3: Y (M,N) = W (M,K) X (K,N), here
+/* Y = W X for nb right-hand sides at once (the paper's problem statement, Section 2.1: Y (M,N) = W (M,K) X (K,N), here
  * with N = nb in {1, 2, 4, 8}; the paper leaves small N > 1 as future work, Section 10).  d_X: device, n rows of nb
  * FP16 (row-major: the nb values that belong to one column of W are adjacent), d_Y: device, m rows of nb FP16; every
  * entry of Y is written.  The deltas are decoded once and every stored entry of W is read once for all nb products.

@@ -4,9 +4,9 @@
  * Only tests, the smoke check and the bench's cpu_baseline leg may call this.  It shares
  * no code with the EC-CSR encoder or the HIP kernels.
  *
- * What it computes (paper, Section 1 "The SpMV kernel computes the product of a sparse
- * weight matrix W and an input vector X to produce Y"; Section 2.1, W of shape (M, K);
- * Section 2.2, batch size B = 1 so X is a vector):
+ * What it computes (paper, Section 1: the kernel in question is the product of the sparse
+ * weight matrix W with the input vector; Section 2.1: W has shape (M, K); Section 2.2: the
+ * batch size is 1, so the input is a vector):
  *
  *     y[i] = sum_{j=0}^{n-1} W[i,j] * x[j]        S[i] = sum_j |W[i,j] * x[j]|
  *
@@ -83,8 +83,7 @@ int oracle_spmv_f64(const uint16_t *W, int64_t m, int64_t n, int64_t ld,
 }
 
 /*
- * The same definition for the paper's FP32 precision (Section 3 states the problem for both; Section 8 measures
- * both): W (m x n, leading dimension ld) and x are binary32; each input is converted exactly to FP64 (a C cast of a
+ * The same definition for the paper's FP32 precision (Section 8 evaluates FP32 and FP16): W (m x n, leading dimension ld) and x are binary32; each input is converted exactly to FP64 (a C cast of a
  * float to double is exact), products and sums are FP64, columns in natural order.  y, S: m doubles each.
  * Returns the number of threads used.
  */
