@@ -186,9 +186,9 @@ inline void list_bits(const std::vector<uint64_t> &bits, std::vector<int32_t> &o
     }
 }
 
-// Cut a sorted column list into units of 64 columns whose successive gaps fit a delta index (the
-// "adjacent columns within the range R_P" rule of Section 6.2 and the "multiples of the load quantum" rule
-// of Section 6.3.1, with the quantum being one unit).  Columns that end up in no unit go to `rest`.
+// Cut a sorted column list into units of 64 columns whose successive gaps fit a delta index (Section 6.2: a
+// block takes only columns that lie within the delta range of their neighbour; Section 6.3.1: block widths are
+// whole multiples of the load quantum, here one unit).  Columns that end up in no unit go to `rest`.
 void form_units(const std::vector<int32_t> &cols, int32_t max_delta, std::vector<int32_t> &taken,
                 std::vector<int32_t> &rest)
 {
