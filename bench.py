@@ -78,7 +78,7 @@ def main():
         args.no_extras = args.no_cpu_baseline = True
     if args.gpus != 1:
         print(f"bench.py: this build runs on one GPU; --gpus {args.gpus} is not supported "
-              "(the path shards by row panels, see DESIGN.md), exiting", file=sys.stderr)
+              "(every run uses one GPU; across GPUs the path would shard by row panels), exiting", file=sys.stderr)
         sys.exit(2)
 
     import torch
