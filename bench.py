@@ -311,6 +311,26 @@ def main():
         out["per_step_us"] = {"launch_mode": args.launch, "steps": nst, "min": round(per[0], 3),
                               "median": round(per[nst // 2], 3), "max": round(per[-1], 3)}
 
+        # clocks while the GPU is busy with the same work, as rocm-smi reports them (context; skipped if unreadable)
+        try:
+            import subprocess
+            smi = subprocess.Popen(["rocm-smi", "--showclocks", "--json"], stdout=subprocess.PIPE,
+                                   stderr=subprocess.DEVNULL, text=True)
+            t_stop = time.time() + 10.0
+            while smi.poll() is None and time.time() < t_stop:
+                for s in range(50):
+                    run_layer(mats[s % copies])
+                torch.cuda.synchronize()
+            if smi.poll() is None:
+                smi.kill()
+            txt = smi.communicate(timeout=5)[0]
+            js = [ln for ln in txt.splitlines() if ln.startswith("{")]
+            if js:
+                card = next(iter(json.loads(js[-1]).values()))
+                out["gpu_clocks_under_load"] = {k.strip(" :"): v.strip("()") for k, v in card.items() if "speed" in k}
+        except Exception:
+            pass
+
         # hot cache: the same layer over and over (working set of one layer still exceeds L2)
         for _ in range(3):
             run_layer(mats[0])
