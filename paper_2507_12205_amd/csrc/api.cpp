@@ -338,28 +338,41 @@ int ecspmv_run_multi(const ecspmv_matrix *A, const void *d_X, void *d_Y, int32_t
     const ecs::Image &im = A->image;
     if (im.value_bits != 16) return ECSPMV_ERR_UNSUPPORTED;           // FP16 images only
     if (im.type_mask & ~3u) return ECSPMV_ERR_UNSUPPORTED;            // 8- or 16-grained sets: registers run out
-    const uint32_t x_bytes = ((uint32_t)im.n * 2u * (uint32_t)nb + 15u) / 16u * 16u;
-    const uint32_t slot_bytes = (im.max_slots * 4u * (uint32_t)nb + 15u) / 16u * 16u;
-    const uint64_t lds = (uint64_t)x_bytes + im.meta_stride + slot_bytes;
     int lim = 0;
     int e = ecs::device_lds_limit(&lim);
     if (e) return hip_status(e);
-    if (lds > (uint64_t)lim) return ECSPMV_ERR_UNSUPPORTED;           // x and the partial sums do not fit LDS
-    ecs::EcsBatch b;
-    std::memset(&b, 0, sizeof(b));
-    b.count = 1;
-    ecs::EcsBatchItem &it = b.item[0];
-    it.image = static_cast<const uint8_t *>(A->d_image);
-    it.x = static_cast<const uint16_t *>(d_X);
-    it.y = static_cast<uint16_t *>(d_Y);
-    it.n = (uint32_t)im.n;
-    it.panel_stride = im.panel_stride;
-    it.meta_stride = im.meta_stride;
-    it.x_bytes = x_bytes;
-    it.block_end = (uint32_t)im.num_panels;
+    // All nb right-hand sides in one launch if X and the partial sums fit LDS; otherwise several launches of nb / 2
+    // or nb / 4 right-hand sides each, which read their columns of X and write their columns of Y with the row
+    // stride nb (the image is then read once per launch).
+    uint32_t per = (uint32_t)nb, x_bytes = 0;
+    uint64_t lds = 0;
+    for (;; per /= 2) {
+        x_bytes = ((uint32_t)im.n * 2u * per + 15u) / 16u * 16u;
+        const uint32_t slot_bytes = (im.max_slots * 4u * per + 15u) / 16u * 16u;
+        lds = (uint64_t)x_bytes + im.meta_stride + slot_bytes;
+        if (lds <= (uint64_t)lim) break;
+        if (per == 2) return ECSPMV_ERR_UNSUPPORTED;                  // not even two right-hand sides fit
+    }
     const uint32_t threads = im.threads_per_wg ? (uint32_t)im.threads_per_wg : 1024u;
-    return hip_status(ecs::launch_ecspmv_multi(b, threads, (uint32_t)lds, im.type_mask, (uint32_t)im.delta_bits,
-                                               (uint32_t)nb, stream));
+    for (uint32_t c0 = 0; c0 < (uint32_t)nb; c0 += per) {
+        ecs::EcsBatch b;
+        std::memset(&b, 0, sizeof(b));
+        b.count = 1;
+        ecs::EcsBatchItem &it = b.item[0];
+        it.image = static_cast<const uint8_t *>(A->d_image);
+        it.x = static_cast<const uint16_t *>(d_X) + c0;
+        it.y = static_cast<uint16_t *>(d_Y) + c0;
+        it.n = (uint32_t)im.n;
+        it.panel_stride = im.panel_stride;
+        it.meta_stride = im.meta_stride;
+        it.x_bytes = x_bytes;
+        it.block_end = (uint32_t)im.num_panels;
+        it.row_stride = (uint32_t)nb;                                 // of X and Y, in elements
+        int s = hip_status(ecs::launch_ecspmv_multi(b, threads, (uint32_t)lds, im.type_mask, (uint32_t)im.delta_bits, per,
+                                                    stream));
+        if (s) return s;
+    }
+    return ECSPMV_OK;
 }
 
 int ecspmv_csr_build_dense(const uint16_t *W, int64_t m, int64_t n, int64_t ld, ecspmv_csr **out)

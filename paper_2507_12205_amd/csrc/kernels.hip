@@ -435,7 +435,7 @@ __global__ __launch_bounds__(1024) void ecspmv_kernel(const uint32_t count, cons
     // carry several SpMVs.
     ecs::EcsBatchItem it;
     it.image = image0, it.x = x0, it.y = y0, it.n = n0, it.panel_stride = panel_stride0, it.meta_stride = meta_stride0;
-    it.x_bytes = x_bytes0, it.block_end = block_end0, it.pad_ = 0;
+    it.x_bytes = x_bytes0, it.block_end = block_end0, it.row_stride = 0;
     uint32_t block0 = 0;
     if (count > 1) {
         uint32_t k = 0;
@@ -448,6 +448,13 @@ __global__ __launch_bounds__(1024) void ecspmv_kernel(const uint32_t count, cons
     const uint16_t *__restrict__ x = it.x;
     uint16_t *__restrict__ y = it.y;
     const uint32_t n = it.n * NB * (VW / 2), meta_stride = it.meta_stride, x_bytes = it.x_bytes;   // n: 2-byte units of x
+    // several right-hand sides: elements from one row of X (and of Y) to the next.  NB when the launch handles all
+    // columns of X; larger when X has more columns than this launch takes.
+    uint32_t ld = NB;
+    if constexpr (NB > 1) {
+        const uint32_t given = batch.item[0].row_stride;
+        if (given) ld = given;
+    }
 
     extern __shared__ uint4 lds4[];
     uint8_t *lds = reinterpret_cast<uint8_t *>(lds4);
@@ -479,7 +486,7 @@ __global__ __launch_bounds__(1024) void ecspmv_kernel(const uint32_t count, cons
     const uint4 *p4 = reinterpret_cast<const uint4 *>(panel);
     const uint32_t nmeta = meta_stride / 16u;
     const uint32_t nvec = n / 8u;
-    const bool x_fast = (reinterpret_cast<uintptr_t>(x) & 15) == 0 && nvec > 0;
+    const bool x_fast = (reinterpret_cast<uintptr_t>(x) & 15) == 0 && nvec > 0 && ld == NB;
     const uint4 *xsrc = reinterpret_cast<const uint4 *>(x);
     const uint32_t ntot = nmeta + (x_fast ? nvec : 0u);         // nmeta >= 1
     // Threads beyond the end of the list bring a piece a second time (same bytes to the same place).  Which one
@@ -538,8 +545,21 @@ __global__ __launch_bounds__(1024) void ecspmv_kernel(const uint32_t count, cons
         else
             lds4[idx - nmeta] = xsrc[idx - nmeta];
     }
-    // what 16-byte pieces do not cover: the last n % 8 entries of x, or all of x if it is not 16-byte aligned
-    for (uint32_t i = (x_fast ? nvec * 8u : 0u) + tid; i < n; i += nt) xs[i] = x[i];
+    // what 16-byte pieces do not cover: the last n % 8 entries of x, or all of x if it is not 16-byte aligned or its
+    // rows are longer than the NB values this launch takes
+    if (NB > 1 && ld != NB) {
+        // one load of NB values per row of X where the alignment allows it
+        typedef uint16_t rowvec __attribute__((ext_vector_type(NB)));
+        if ((reinterpret_cast<uintptr_t>(x) & (2u * NB - 1u)) == 0 && ld % NB == 0) {
+            const rowvec *src = reinterpret_cast<const rowvec *>(x);
+            rowvec *dst = reinterpret_cast<rowvec *>(xs);
+            for (uint32_t i = tid; i < it.n; i += nt) dst[i] = src[i * (ld / NB)];
+        } else {
+            for (uint32_t i = tid; i < n; i += nt) xs[i] = x[(i / NB) * ld + (i % NB)];
+        }
+    } else {
+        for (uint32_t i = (x_fast ? nvec * 8u : 0u) + tid; i < n; i += nt) xs[i] = x[i];
+    }
     __syncthreads();
 
     if constexpr (residual_late) rs.prologue(c, hdr, dealt);
@@ -575,7 +595,7 @@ __global__ __launch_bounds__(1024) void ecspmv_kernel(const uint32_t count, cons
         for (int b = 0; b < NB; ++b) {
             const float t = row16_allreduce(sum[b]);
             if constexpr (VW == 2) {
-                if (j == 0) y[(row0 + r) * NB + b] = __half_as_ushort(__float2half_rn(t));
+                if (j == 0) y[(row0 + r) * ld + b] = __half_as_ushort(__float2half_rn(t));
             } else {
                 if (j == 0) reinterpret_cast<float *>(y)[row0 + r] = t;
             }

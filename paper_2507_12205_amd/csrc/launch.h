@@ -13,7 +13,7 @@ struct EcsBatchItem {
     uint16_t *y;              // device, m FP16
     uint32_t n, panel_stride, meta_stride, x_bytes;
     uint32_t block_end;       // workgroups [previous item's block_end, block_end) belong to this item
-    uint32_t pad_;
+    uint32_t row_stride;      // several right-hand sides: elements from one row of X (and Y) to the next; 0 = packed
 };
 #define ECS_MAX_BATCH 16
 struct EcsBatch {

@@ -27,14 +27,16 @@ def make_X(n, nb, seed):
     return np.stack([gen.make_vector(n, seed=seed + b) for b in range(nb)], axis=1).copy()      # (n, nb) row-major
 
 
-def check(E, W, nb, label, seed=100, **opts):
+def check(E, W, nb, label, seed=100, x_offset=0, **opts):
     import torch
-    print(f"[case] multi {label} nb={nb} shape={W.shape}", flush=True)
+    print(f"[case] multi {label} nb={nb} shape={W.shape} x_offset={x_offset}", flush=True)
     m, n = W.shape
     A = E.ecspmv_build_dense(W, E.make_opts(**opts))
     E.device.upload(A)
     X = make_X(n, nb, seed)
-    Xd = torch.from_numpy(X.view(np.int16)).cuda().view(torch.float16)
+    flat = torch.zeros(n * nb + 16, dtype=torch.float16, device="cuda")       # x_offset: X starts that many elements in
+    Xd = flat[x_offset:x_offset + n * nb].view(n, nb)
+    Xd.copy_(torch.from_numpy(X.view(np.int16)).cuda().view(torch.float16))
     Yd = torch.full((m, nb), float("nan"), dtype=torch.float16, device="cuda")
     E.device.run_multi(A, Xd, Yd)
     torch.cuda.synchronize()
@@ -98,6 +100,16 @@ def test_full_size_projection(E):
     W = gen.make_matrix(gen.config(3), 0)
     check(E, W, 4, "cfg3 q full size", delta_bits=4)
     check(E, W, 8, "cfg3 q full size 8-bit", delta_bits=8, max_granularity=4)
+
+
+def test_columns_split_over_launches(E):
+    """X too wide for LDS: the call runs as several launches of nb / 2 or nb / 4 right-hand sides, each reading its
+    columns of X and writing its columns of Y with the row stride nb.  Same band, same bits per column."""
+    for (m, n, nb) in ((96, 12000, 8), (64, 30000, 4), (64, 30000, 8), (40, 13824, 8)):
+        W, _ = gen.small_random(m, n, 0.05, 11 + nb)
+        A = check(E, W, nb, f"split {m}x{n}", delta_bits=4, max_granularity=2)
+        check(E, W, nb, f"split {m}x{n}, X two bytes off a 16-byte boundary", x_offset=1, delta_bits=4, max_granularity=2)
+        assert 2 * n * nb + A.ecspmv_stats().meta_stride > 160 * 1024         # it could not have run as one launch
 
 
 def test_refusals(E):
