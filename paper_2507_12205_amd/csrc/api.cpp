@@ -337,7 +337,7 @@ int ecspmv_run_multi(const ecspmv_matrix *A, const void *d_X, void *d_Y, int32_t
     if (!A->d_image) return ECSPMV_ERR_NOT_UPLOADED;
     const ecs::Image &im = A->image;
     if (im.value_bits != 16) return ECSPMV_ERR_UNSUPPORTED;           // FP16 images only
-    if (im.type_mask & ~3u) return ECSPMV_ERR_UNSUPPORTED;            // 8- or 16-grained sets: registers run out
+    if (im.type_mask & ~7u) return ECSPMV_ERR_UNSUPPORTED;            // a 16-grained set: registers run out
     int lim = 0;
     int e = ecs::device_lds_limit(&lim);
     if (e) return hip_status(e);

@@ -705,7 +705,7 @@ static int launch_tm(const EcsBatch &batch, uint32_t threads, uint32_t lds_bytes
                            : launch_b<TM, 8, false>(batch, threads, lds_bytes, stream);
 }
 
-// several right-hand sides: one matrix per launch, the widest staging variant, images with 4-grained sets at most
+// several right-hand sides: one matrix per launch, the widest staging variant, images with 8-grained sets at most
 template <int TM, int DB>
 static int launch_nb(const EcsBatch &batch, uint32_t threads, uint32_t lds_bytes, uint32_t nb, void *stream)
 {
@@ -720,12 +720,14 @@ static int launch_nb(const EcsBatch &batch, uint32_t threads, uint32_t lds_bytes
 int launch_ecspmv_multi(const EcsBatch &batch, uint32_t threads, uint32_t lds_bytes, uint32_t type_mask,
                         uint32_t delta_bits, uint32_t nb, void *stream)
 {
-    const int top = (type_mask & 2) ? 3 : (type_mask & 1) ? 1 : 0;
+    const int top = (type_mask & 4) ? 7 : (type_mask & 2) ? 3 : (type_mask & 1) ? 1 : 0;
     if (delta_bits == 4) {
+        if (top == 7) return launch_nb<7, 4>(batch, threads, lds_bytes, nb, stream);
         if (top == 3) return launch_nb<3, 4>(batch, threads, lds_bytes, nb, stream);
         if (top == 1) return launch_nb<1, 4>(batch, threads, lds_bytes, nb, stream);
         return launch_nb<0, 4>(batch, threads, lds_bytes, nb, stream);
     }
+    if (top == 7) return launch_nb<7, 8>(batch, threads, lds_bytes, nb, stream);
     if (top == 3) return launch_nb<3, 8>(batch, threads, lds_bytes, nb, stream);
     if (top == 1) return launch_nb<1, 8>(batch, threads, lds_bytes, nb, stream);
     return launch_nb<0, 8>(batch, threads, lds_bytes, nb, stream);

@@ -66,6 +66,12 @@ def test_configs_reduced(E, nb, bits):
         if bits == 8 and cid in (1, 3):
             st = A.ecspmv_stats()
             assert st.nnz_by_g[1] > 0 and st.nnz_by_g[3] == 0          # block sets take part
+    # the library's default cap on g (8): identical rows give an 8-grained set
+    W = np.zeros((40, 700), dtype=np.float16)
+    W[:, ::2] = gen.small_random(1, 350, 1.0, 5)[0]
+    W[3:11, 1::4] = 0.25
+    A = check(E, W, nb, f"8-grained/bits{bits}", delta_bits=bits, flags=E.binding.FLAG_KEEP_SMALL_SETS)
+    assert A.ecspmv_stats().nnz_by_g[3] > 0
 
 
 @pytest.mark.parametrize("nb", [2, 4, 8])
@@ -116,9 +122,9 @@ def test_refusals(E):
     import torch
     B = E.binding
     W = np.zeros((16, 3000), dtype=np.float16)
-    W[:, ::3] = 1.0                                                    # identical rows: an 8-grained set by default
-    A = E.ecspmv_build_dense(W)
-    assert A.ecspmv_stats().nnz_by_g[3] > 0
+    W[:, ::3] = 1.0                                                    # identical rows: a 16-grained set if asked for
+    A = E.ecspmv_build_dense(W, E.make_opts(max_granularity=16))
+    assert A.ecspmv_stats().nnz_by_g[4] > 0
     E.device.upload(A)
     X = torch.zeros((3000, 2), dtype=torch.float16, device="cuda")
     Y = torch.zeros((16, 2), dtype=torch.float16, device="cuda")

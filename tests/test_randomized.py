@@ -83,7 +83,7 @@ def test_parity_random_gpu():
             for t in ys:
                 assert np.array_equal(t.cpu().numpy().view(np.uint16), y.view(np.uint16)), (it, "batch of three")
         nb = int(rng.choice([0, 0, 2, 4, 8]))       # now and then: several right-hand sides, FP32 values
-        if nb and A.ecspmv_stats().nnz_by_g[3] + A.ecspmv_stats().nnz_by_g[4] == 0:
+        if nb and A.ecspmv_stats().nnz_by_g[4] == 0:
             X = np.stack([x] + [rng.standard_normal(len(x)).astype(np.float16) for _ in range(nb - 1)], axis=1).copy()
             Xd = torch.from_numpy(X.view(np.int16)).cuda().view(torch.float16)
             Yd = torch.full((W.shape[0], nb), float("nan"), dtype=torch.float16, device="cuda")
