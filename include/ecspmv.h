@@ -167,8 +167,9 @@ int ecspmv_run_batch(const ecspmv_matrix *const *As, const void *const *d_xs, vo
  * One kernel launch, asynchronous on `stream`, no allocation.  nb = 1 is ecspmv_run.  Where 2*n*nb bytes of X plus
  * 4*nb bytes per partial sum do not fit the LDS of a compute unit, the call runs as 2 or 4 launches of nb/2 or nb/4
  * right-hand sides each (same X, Y and results; the image is then read once per launch).
- * ECSPMV_ERR_UNSUPPORTED for FP32 matrices, if the image holds a 16-grained block set (build with
- * max_granularity <= 8, the default, for this call) or if not even two right-hand sides fit LDS; ECSPMV_ERR_INVALID for other nb. */
+ * For a matrix built with ecspmv_build_*_f32, X and Y are FP32 (and 4*n*nb bytes of X count for LDS).
+ * ECSPMV_ERR_UNSUPPORTED if the image holds a 16-grained block set, or an 8-grained one with FP32 values (the default
+ * build options produce neither), or if not even two right-hand sides fit LDS; ECSPMV_ERR_INVALID for other nb. */
 int ecspmv_run_multi(const ecspmv_matrix *A, const void *d_X, void *d_Y, int32_t nb, void *stream);
 
 /* ---- comparison: plain CSR (int32 column index + FP16 value per entry, one wavefront per row) ------- */

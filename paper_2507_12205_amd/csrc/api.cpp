@@ -333,11 +333,13 @@ int ecspmv_run_multi(const ecspmv_matrix *A, const void *d_X, void *d_Y, int32_t
     if (!A || !d_X || !d_Y) return ECSPMV_ERR_INVALID;
     if (nb == 1) return ecspmv_run(A, d_X, d_Y, stream);
     if (nb != 2 && nb != 4 && nb != 8) return ECSPMV_ERR_INVALID;
-    if ((reinterpret_cast<uintptr_t>(d_X) & 1) || (reinterpret_cast<uintptr_t>(d_Y) & 1)) return ECSPMV_ERR_INVALID;
-    if (!A->d_image) return ECSPMV_ERR_NOT_UPLOADED;
     const ecs::Image &im = A->image;
-    if (im.value_bits != 16) return ECSPMV_ERR_UNSUPPORTED;           // FP16 images only
-    if (im.type_mask & ~7u) return ECSPMV_ERR_UNSUPPORTED;            // a 16-grained set: registers run out
+    const uint32_t vw = (uint32_t)im.value_bits / 8u;                 // bytes per value of W, X and Y
+    if ((reinterpret_cast<uintptr_t>(d_X) & (vw - 1u)) || (reinterpret_cast<uintptr_t>(d_Y) & (vw - 1u)))
+        return ECSPMV_ERR_INVALID;
+    if (!A->d_image) return ECSPMV_ERR_NOT_UPLOADED;
+    // registers run out with a 16-grained set, and with an 8-grained one if the values are FP32
+    if (im.type_mask & (vw == 4 ? ~3u : ~7u)) return ECSPMV_ERR_UNSUPPORTED;
     int lim = 0;
     int e = ecs::device_lds_limit(&lim);
     if (e) return hip_status(e);
@@ -347,7 +349,7 @@ int ecspmv_run_multi(const ecspmv_matrix *A, const void *d_X, void *d_Y, int32_t
     uint32_t per = (uint32_t)nb, x_bytes = 0;
     uint64_t lds = 0;
     for (;; per /= 2) {
-        x_bytes = ((uint32_t)im.n * 2u * per + 15u) / 16u * 16u;
+        x_bytes = ((uint32_t)im.n * vw * per + 15u) / 16u * 16u;
         const uint32_t slot_bytes = (im.max_slots * 4u * per + 15u) / 16u * 16u;
         lds = (uint64_t)x_bytes + im.meta_stride + slot_bytes;
         if (lds <= (uint64_t)lim) break;
@@ -360,16 +362,16 @@ int ecspmv_run_multi(const ecspmv_matrix *A, const void *d_X, void *d_Y, int32_t
         b.count = 1;
         ecs::EcsBatchItem &it = b.item[0];
         it.image = static_cast<const uint8_t *>(A->d_image);
-        it.x = static_cast<const uint16_t *>(d_X) + c0;
-        it.y = static_cast<uint16_t *>(d_Y) + c0;
+        it.x = reinterpret_cast<const uint16_t *>(static_cast<const uint8_t *>(d_X) + (size_t)c0 * vw);
+        it.y = reinterpret_cast<uint16_t *>(static_cast<uint8_t *>(d_Y) + (size_t)c0 * vw);
         it.n = (uint32_t)im.n;
         it.panel_stride = im.panel_stride;
         it.meta_stride = im.meta_stride;
         it.x_bytes = x_bytes;
         it.block_end = (uint32_t)im.num_panels;
         it.row_stride = (uint32_t)nb;                                 // of X and Y, in elements
-        int s = hip_status(ecs::launch_ecspmv_multi(b, threads, (uint32_t)lds, im.type_mask, (uint32_t)im.delta_bits, per,
-                                                    stream));
+        int s = hip_status(ecs::launch_ecspmv_multi(b, threads, (uint32_t)lds, im.type_mask, (uint32_t)im.delta_bits,
+                                                    (uint32_t)im.value_bits, per, stream));
         if (s) return s;
     }
     return ECSPMV_OK;

@@ -97,8 +97,19 @@ template <int NB, int VW>
 __device__ __forceinline__ void gather_x(const uint16_t *xs, uint32_t col, float (&xv)[NB])
 {
     if constexpr (VW == 4) {
-        static_assert(NB == 1, "several right-hand sides are built for FP16 only");
-        xv[0] = reinterpret_cast<const float *>(xs)[col];
+        const float *xf = reinterpret_cast<const float *>(xs);
+        if constexpr (NB == 1) {
+            xv[0] = xf[col];
+        } else if constexpr (NB == 2) {
+            const float2 w = *reinterpret_cast<const float2 *>(xf + 2u * col);
+            xv[0] = w.x, xv[1] = w.y;
+        } else {
+#pragma unroll
+            for (int q = 0; q < NB / 4; ++q) {
+                const float4 w = *reinterpret_cast<const float4 *>(xf + NB * col + 4 * q);
+                xv[4 * q] = w.x, xv[4 * q + 1] = w.y, xv[4 * q + 2] = w.z, xv[4 * q + 3] = w.w;
+            }
+        }
     } else if constexpr (NB == 1) {
         xv[0] = half_bits_to_float(xs[col]);
     } else if constexpr (NB == 2) {
@@ -548,14 +559,18 @@ __global__ __launch_bounds__(1024) void ecspmv_kernel(const uint32_t count, cons
     // what 16-byte pieces do not cover: the last n % 8 entries of x, or all of x if it is not 16-byte aligned or its
     // rows are longer than the NB values this launch takes
     if (NB > 1 && ld != NB) {
-        // one load of NB values per row of X where the alignment allows it
-        typedef uint16_t rowvec __attribute__((ext_vector_type(NB)));
-        if ((reinterpret_cast<uintptr_t>(x) & (2u * NB - 1u)) == 0 && ld % NB == 0) {
+        // one load of NB values per row of X where the alignment allows it (ld counts values of VW bytes)
+        typedef uint16_t rowvec __attribute__((ext_vector_type(NB * VW / 2)));
+        if ((reinterpret_cast<uintptr_t>(x) & (uint32_t)(VW * NB - 1)) == 0 && ld % NB == 0) {
             const rowvec *src = reinterpret_cast<const rowvec *>(x);
             rowvec *dst = reinterpret_cast<rowvec *>(xs);
             for (uint32_t i = tid; i < it.n; i += nt) dst[i] = src[i * (ld / NB)];
-        } else {
+        } else if constexpr (VW == 2) {
             for (uint32_t i = tid; i < n; i += nt) xs[i] = x[(i / NB) * ld + (i % NB)];
+        } else {
+            const uint32_t *src = reinterpret_cast<const uint32_t *>(x);
+            uint32_t *dst = reinterpret_cast<uint32_t *>(xs);
+            for (uint32_t i = tid; i < it.n * NB; i += nt) dst[i] = src[(i / NB) * ld + (i % NB)];
         }
     } else {
         for (uint32_t i = (x_fast ? nvec * 8u : 0u) + tid; i < n; i += nt) xs[i] = x[i];
@@ -597,7 +612,7 @@ __global__ __launch_bounds__(1024) void ecspmv_kernel(const uint32_t count, cons
             if constexpr (VW == 2) {
                 if (j == 0) y[(row0 + r) * ld + b] = __half_as_ushort(__float2half_rn(t));
             } else {
-                if (j == 0) reinterpret_cast<float *>(y)[row0 + r] = t;
+                if (j == 0) reinterpret_cast<float *>(y)[(row0 + r) * ld + b] = t;
             }
         }
     }
@@ -706,21 +721,33 @@ static int launch_tm(const EcsBatch &batch, uint32_t threads, uint32_t lds_bytes
 }
 
 // several right-hand sides: one matrix per launch, the widest staging variant, images with 8-grained sets at most
-template <int TM, int DB>
+template <int TM, int DB, int VW = 2>
 static int launch_nb(const EcsBatch &batch, uint32_t threads, uint32_t lds_bytes, uint32_t nb, void *stream)
 {
     switch (nb) {
-    case 2: return launch_k<TM, DB, false, 4, 2>(batch, threads, lds_bytes, stream);
-    case 4: return launch_k<TM, DB, false, 4, 4>(batch, threads, lds_bytes, stream);
-    case 8: return launch_k<TM, DB, false, 4, 8>(batch, threads, lds_bytes, stream);
+    case 2: return launch_k<TM, DB, false, 4, 2, VW>(batch, threads, lds_bytes, stream);
+    case 4: return launch_k<TM, DB, false, 4, 4, VW>(batch, threads, lds_bytes, stream);
+    case 8: return launch_k<TM, DB, false, 4, 8, VW>(batch, threads, lds_bytes, stream);
     default: return (int)hipErrorInvalidValue;
     }
 }
 
 int launch_ecspmv_multi(const EcsBatch &batch, uint32_t threads, uint32_t lds_bytes, uint32_t type_mask,
-                        uint32_t delta_bits, uint32_t nb, void *stream)
+                        uint32_t delta_bits, uint32_t value_bits, uint32_t nb, void *stream)
 {
     const int top = (type_mask & 4) ? 7 : (type_mask & 2) ? 3 : (type_mask & 1) ? 1 : 0;
+    if (value_bits == 32) {                          // FP32 values: images with 4-grained sets at most
+        if (delta_bits == 4) {
+            if (top == 3) return launch_nb<3, 4, 4>(batch, threads, lds_bytes, nb, stream);
+            if (top == 1) return launch_nb<1, 4, 4>(batch, threads, lds_bytes, nb, stream);
+            if (top == 0) return launch_nb<0, 4, 4>(batch, threads, lds_bytes, nb, stream);
+            return (int)hipErrorInvalidValue;
+        }
+        if (top == 3) return launch_nb<3, 8, 4>(batch, threads, lds_bytes, nb, stream);
+        if (top == 1) return launch_nb<1, 8, 4>(batch, threads, lds_bytes, nb, stream);
+        if (top == 0) return launch_nb<0, 8, 4>(batch, threads, lds_bytes, nb, stream);
+        return (int)hipErrorInvalidValue;
+    }
     if (delta_bits == 4) {
         if (top == 7) return launch_nb<7, 4>(batch, threads, lds_bytes, nb, stream);
         if (top == 3) return launch_nb<3, 4>(batch, threads, lds_bytes, nb, stream);

@@ -25,9 +25,9 @@ struct EcsBatch {
 int launch_ecspmv(const EcsBatch &batch, uint32_t threads, uint32_t lds_bytes, uint32_t type_mask, uint32_t delta_bits,
                   uint32_t value_bits, void *stream);
 // One matrix, nb = 2, 4 or 8 right-hand sides (x: n rows of nb values, y: m rows of nb values); type_mask must not
-// have the bit of the 16-grained set.
+// have the bit of the 16-grained set, nor that of the 8-grained set with FP32 values.
 int launch_ecspmv_multi(const EcsBatch &batch, uint32_t threads, uint32_t lds_bytes, uint32_t type_mask,
-                        uint32_t delta_bits, uint32_t nb, void *stream);
+                        uint32_t delta_bits, uint32_t value_bits, uint32_t nb, void *stream);
 int launch_csr(const void *d_rowptr, const void *d_col, const void *d_val, const void *d_x, void *d_y, uint32_t m,
                void *stream);
 int launch_stream_read(const void *d_buf, uint64_t bytes, void *d_out, uint32_t num_wg, void *stream);

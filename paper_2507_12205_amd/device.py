@@ -31,8 +31,10 @@ def run(mat: B.Matrix, x: torch.Tensor, y: torch.Tensor, stream=None) -> torch.T
 
 
 def run_multi(mat: B.Matrix, X: torch.Tensor, Y: torch.Tensor, stream=None) -> torch.Tensor:
-    """Y = W X for X of shape (n, nb), Y of shape (m, nb), both FP16, row-major, nb in {1, 2, 4, 8}."""
-    assert X.dtype == torch.float16 and Y.dtype == torch.float16 and X.is_cuda and Y.is_cuda
+    """Y = W X for X of shape (n, nb), Y of shape (m, nb), row-major, nb in {1, 2, 4, 8}; FP16, or FP32 for a matrix
+    built from FP32 values."""
+    want = torch.float32 if mat.ecspmv_stats().value_bits == 32 else torch.float16
+    assert X.dtype == want and Y.dtype == want and X.is_cuda and Y.is_cuda
     assert X.dim() == 2 and Y.dim() == 2 and X.shape[1] == Y.shape[1] and X.is_contiguous() and Y.is_contiguous()
     mat.ecspmv_run_multi(X.data_ptr(), Y.data_ptr(), int(X.shape[1]), _stream_handle(stream))
     return Y

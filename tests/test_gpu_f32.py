@@ -145,7 +145,66 @@ def test_batch_with_fp16_and_fp32_matrices(E):
     torch.cuda.synchronize()
     for y, l in zip(ys, lone):
         assert torch.equal(y, l)
-    X = torch.zeros((900 + 100, 2), dtype=torch.float16, device="cuda")
-    with pytest.raises(E.EcspmvError) as e:                           # several right-hand sides: FP16 matrices only
-        mats[1].ecspmv_run_multi(X.data_ptr(), X.data_ptr(), 2)
+
+
+def check_multi(E, W, nb, label, x_offset=0, **opts):
+    """Y = W X with FP32 values: every column inside the band of the FP32 oracle, and bit-equal to the single-vector
+    launch on that column."""
+    import torch
+    print(f"[case] f32 multi {label} nb={nb} shape={W.shape} x_offset={x_offset}", flush=True)
+    m, n = W.shape
+    A = E.ecspmv_build_dense_f32(W, E.make_opts(**opts))
+    E.device.upload(A)
+    rng = np.random.default_rng(nb + n)
+    X = rng.standard_normal((n, nb)).astype(np.float32)
+    flat = torch.zeros(n * nb + 16, dtype=torch.float32, device="cuda")
+    Xd = flat[x_offset:x_offset + n * nb].view(n, nb)
+    Xd.copy_(torch.from_numpy(X).cuda())
+    Yd = torch.full((m, nb), float("nan"), dtype=torch.float32, device="cuda")
+    E.device.run_multi(A, Xd, Yd)
+    torch.cuda.synchronize()
+    Y = Yd.cpu().numpy()
+    assert not np.isnan(Y).any(), "an entry of Y was not written"
+    yd = torch.empty(m, dtype=torch.float32, device="cuda")
+    for b in range(nb):
+        xb = np.ascontiguousarray(X[:, b])
+        y_ref, S = orc.spmv_oracle_f32(W, xb)
+        err = np.abs(Y[:, b].astype(np.float64) - y_ref)
+        assert np.all(err <= REL * S + ABS) and np.all(err <= 2.0 ** -17 * S + 1e-9), (label, b)
+        E.device.run(A, torch.from_numpy(xb).cuda(), yd)
+        torch.cuda.synchronize()
+        assert np.array_equal(yd.cpu().numpy().view(np.uint32), np.ascontiguousarray(Y[:, b]).view(np.uint32)), (label, b)
+    return A
+
+
+@pytest.mark.parametrize("nb", [2, 4, 8])
+@pytest.mark.parametrize("bits", [4, 8])
+def test_several_right_hand_sides(E, nb, bits):
+    for cid, div in ((0, 1), (1, 4), (3, 8)):
+        cfg = gen.scaled(gen.config(cid), div) if div > 1 else gen.config(cid)
+        check_multi(E, make_f32(gen.make_matrix(cfg, 0), cid), nb, f"cfg{cid}/div{div}/bits{bits}", delta_bits=bits)
+    W = np.zeros((24, 900), dtype=np.float32)                        # identical rows: 4-grained sets take part
+    W[:, ::2] = np.linspace(0.5, 1.5, 450, dtype=np.float32)
+    A = check_multi(E, W, nb, f"4-grained/bits{bits}", delta_bits=bits, flags=E.binding.FLAG_KEEP_SMALL_SETS)
+    assert A.ecspmv_stats().nnz_by_g[2] > 0
+
+
+def test_several_right_hand_sides_split_and_refused(E):
+    import torch
+    # 4 * n * nb bytes of X exceed LDS: two or four launches with a row stride, aligned and not
+    for (m, n, nb) in ((64, 9000, 8), (48, 15000, 4)):
+        W = make_f32(gen.small_random(m, n, 0.05, 5 + nb)[0], 9)
+        A = check_multi(E, W, nb, f"split {m}x{n}", delta_bits=4, max_granularity=2)
+        assert 4 * n * nb + A.ecspmv_stats().meta_stride > 160 * 1024
+        check_multi(E, W, nb, f"split {m}x{n}, X four bytes off a 16-byte boundary", x_offset=1, delta_bits=4, max_granularity=2)
+    W = np.zeros((16, 3000), dtype=np.float32)
+    W[:, ::3] = 1.0                                                  # identical rows: an 8-grained set if asked for
+    A = E.ecspmv_build_dense_f32(W, E.make_opts(max_granularity=8))
+    assert A.ecspmv_stats().nnz_by_g[3] > 0
+    E.device.upload(A)
+    X = torch.zeros((3000, 2), dtype=torch.float32, device="cuda")
+    Y = torch.zeros((16, 2), dtype=torch.float32, device="cuda")
+    with pytest.raises(E.EcspmvError) as e:
+        A.ecspmv_run_multi(X.data_ptr(), Y.data_ptr(), 2)
     assert e.value.status == E.binding.ERR_UNSUPPORTED
+    torch.cuda.synchronize()
