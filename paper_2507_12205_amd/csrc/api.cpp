@@ -84,10 +84,6 @@ int finish_build(const ecs::Csr &A, const ecs::BuildParams &bp, ecspmv_matrix **
     return ECSPMV_OK;
 }
 
-}  // namespace
-
-namespace {
-
 // shared by ecspmv_decode (FP16 images, 16-bit values out) and ecspmv_decode_f32 (FP32 images, 32-bit values out)
 template <typename T>
 int decode_t(const ecspmv_matrix *A, int value_bits, int64_t *nnz, int32_t *rows, int32_t *cols, T *vals)
