@@ -229,7 +229,9 @@ def main():
     default_build = not (args.max_granularity or args.panels or args.threads_per_wg or args.delta_bits != 4)
     if args.config == 3 and default_build and os.path.exists(tpath):
         with open(tpath) as f:
-            traffic = json.load(f).get("traffic_bytes_per_launch")
+            tj = json.load(f)
+        traffic = {"single": tj.get("traffic_bytes_per_launch"),
+                   "all": tj.get("traffic_bytes_per_step_launch_all")}.get(args.launch)
 
     out = {
         "metric": "effective HBM GB/s of cold-cache EC-CSR SpMV (EC-CSR bytes + x + y per SpMV / time)",
