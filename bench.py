@@ -218,9 +218,12 @@ def main():
         byt = sum(e["bytes"] for e in lst) / len(lst)
         per_shape[f"{m}x{n}"] = dict(us=round(us, 3), gbps=round(byt / us / 1e3, 1), bytes=int(byt),
                                      cold=bool(tot_img > (300 << 20)), matrices=len(lst))
-    avg_launch_us = us_per_spmv
+    # kernel launches of the timed region in the chosen launch mode
+    launches_per_step = {"single": nshapes, "groups": len(batched["groups"][0]), "all": 1}[args.launch]
+    n_ev = args.steps * launches_per_step
+    avg_launch_us = total_ms * 1e3 / n_ev
     achieved = value
-    byte_sum, n_ev = moved, nlaunch
+    byte_sum = moved
 
     # HBM traffic per launch as counted by rocprofv3 (FETCH_SIZE + WRITE_SIZE runs, see profiles/): measured in
     # separate profiler runs of this same command, so it is read from the committed summary, not sampled here
@@ -271,7 +274,7 @@ def main():
 
     # the same steps submitted with fewer launches (cold rotation, same events)
     out["launch_mode"] = args.launch
-    out["launches_per_step"] = {"single": nshapes, "groups": len(batched["groups"][0]), "all": 1}[args.launch]
+    out["launches_per_step"] = launches_per_step
     alt = {}
     for mode in (() if args.profile_run else ("single", "groups", "all")):
         for w in range(min(args.warmup, copies)):
