@@ -336,21 +336,26 @@ def main():
         except Exception:
             pass
 
-        # hot cache: the same layer over and over (working set of one layer still exceeds L2)
-        for _ in range(3):
-            run_layer(mats[0])
-        torch.cuda.synchronize()
-        ev0.record(stream)
+        # hot cache: one matrix over and over (its image fits the 256 MB Infinity Cache), first matrix of every shape
         reps = max(10, args.steps // 2)
-        for _ in range(reps):
-            for e in mats[0][:1]:
+        hot, seen = {}, set()
+        for e in mats[0]:
+            if (e["m"], e["n"]) in seen:
+                continue
+            seen.add((e["m"], e["n"]))
+            for _ in range(5):
                 e["A"].ecspmv_run(e["x"].data_ptr(), e["y"].data_ptr(), sh)
-        ev1.record(stream)
-        torch.cuda.synchronize()
-        ms = ev0.elapsed_time(ev1)
-        e0 = mats[0][0]
-        out["hot_cache"] = {"matrix": f'{e0["name"]} {e0["m"]}x{e0["n"]}', "us_per_spmv": round(ms * 1e3 / reps, 3),
-                            "gbps": round(e0["bytes"] * reps / (ms * 1e-3) / 1e9, 1)}
+            torch.cuda.synchronize()
+            ev0.record(stream)
+            for _ in range(reps):
+                e["A"].ecspmv_run(e["x"].data_ptr(), e["y"].data_ptr(), sh)
+            ev1.record(stream)
+            torch.cuda.synchronize()
+            ms = ev0.elapsed_time(ev1)
+            hot[f'{e["name"]} {e["m"]}x{e["n"]}'] = {"us_per_spmv": round(ms * 1e3 / reps, 3),
+                                                      "gbps": round(e["bytes"] * reps / (ms * 1e-3) / 1e9, 1)}
+        first = next(iter(hot))
+        out["hot_cache"] = {"matrix": first, **hot[first], "per_shape": hot}
 
         # streaming-read ceiling over the very same images, same rotation
         chk = torch.zeros(1024, dtype=torch.int32, device="cuda")
