@@ -7,6 +7,7 @@ import subprocess
 PKG = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libecspmv.so")
+TRACE_LIB = os.path.join(PKG, "libecspmv_trace.so")     # the same sources with clock stamps compiled in (timeline.py)
 SOURCES = ["api.cpp", "encoder.cpp", "kernels.hip"]
 HEADERS = ["encoder.h", "launch.h", "ecspmv_format.h", os.path.join("..", "..", "include", "ecspmv.h")]
 
@@ -21,6 +22,12 @@ def is_stale() -> bool:
         return True
     t = os.path.getmtime(LIB)
     return any(os.path.getmtime(os.path.join(CSRC, f)) > t for f in SOURCES + HEADERS)
+
+
+def build_all(verbose: bool = False) -> None:
+    """The product library and the stamped one for the timeline script."""
+    build(verbose)
+    build(verbose, extra_flags=("-DECS_TRACE=1",), out=TRACE_LIB)
 
 
 def build(verbose: bool = False, extra_flags=(), out: str = LIB) -> str:

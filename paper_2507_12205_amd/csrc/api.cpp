@@ -1,5 +1,6 @@
 // C ABI of the library (see include/ecspmv.h): argument checks, option defaults, handle bookkeeping.
 #include <algorithm>
+#include <atomic>
 #include <cstring>
 #include <new>
 #include <vector>
@@ -30,6 +31,28 @@ int hip_status(int e)
     if (e == 0) return ECSPMV_OK;
     g_last_hip_error = e;
     return ECSPMV_ERR_HIP;
+}
+
+// LDS a workgroup may use on the current device, asked once per device and kept (the hot calls must not query the
+// runtime on every launch)
+int lds_limit(int *bytes)
+{
+    constexpr int kMaxDev = 64;
+    static std::atomic<int> cached[kMaxDev];
+    int dev = 0;
+    int e = ecs::current_device(&dev);
+    if (e) return e;
+    if (dev >= 0 && dev < kMaxDev) {
+        const int v = cached[dev].load(std::memory_order_relaxed);
+        if (v > 0) {
+            *bytes = v;
+            return 0;
+        }
+    }
+    e = ecs::device_lds_limit(bytes);
+    if (e) return e;
+    if (dev >= 0 && dev < kMaxDev) cached[dev].store(*bytes, std::memory_order_relaxed);
+    return 0;
 }
 
 int map_build_error(int e)
@@ -256,7 +279,7 @@ int ecspmv_upload(ecspmv_matrix *A, void *d_buf, size_t bytes, void *stream)
     if (!A || !d_buf || (reinterpret_cast<uintptr_t>(d_buf) & 255)) return ECSPMV_ERR_INVALID;
     if (bytes < A->image.bytes.size()) return ECSPMV_ERR_TOO_SMALL;
     int lim = 0;
-    int e = ecs::device_lds_limit(&lim);
+    int e = lds_limit(&lim);
     if (e) return hip_status(e);
     if ((int64_t)A->image.lds_bytes > (int64_t)lim) return ECSPMV_ERR_UNSUPPORTED;
     e = ecs::copy_to_device(d_buf, A->image.bytes.data(), A->image.bytes.size(), stream);
@@ -276,14 +299,13 @@ int ecspmv_run_batch(const ecspmv_matrix *const *As, const void *const *d_xs, vo
             return ECSPMV_ERR_INVALID;
         if (!As[i]->d_image) return ECSPMV_ERR_NOT_UPLOADED;
     }
-    std::vector<int32_t> order((size_t)count);
-    for (int32_t i = 0; i < count; ++i) order[(size_t)i] = i;
-    // one launch per run of up to ECS_MAX_BATCH matrices with the same delta width and value width
+    // one launch per run of up to ECS_MAX_BATCH matrices with the same delta width and value width; nothing on
+    // this path allocates or can throw
     for (int32_t base = 0, nb = 0; base < count; base += nb) {
-        const int bits = As[order[(size_t)base]]->image.delta_bits;
-        const int vbits = As[order[(size_t)base]]->image.value_bits;
+        const int bits = As[base]->image.delta_bits;
+        const int vbits = As[base]->image.value_bits;
         for (nb = 1; base + nb < count && nb < ECS_MAX_BATCH; ++nb) {
-            const ecs::Image &nx = As[order[(size_t)(base + nb)]]->image;
+            const ecs::Image &nx = As[base + nb]->image;
             if (nx.delta_bits != bits || nx.value_bits != vbits) break;
         }
         ecs::EcsBatch b;
@@ -291,7 +313,7 @@ int ecspmv_run_batch(const ecspmv_matrix *const *As, const void *const *d_xs, vo
         b.count = (uint32_t)nb;
         uint32_t blocks = 0, lds = 0, mask = 0;
         for (int32_t i = 0; i < nb; ++i) {
-            const int32_t src = order[(size_t)(base + i)];
+            const int32_t src = base + i;
             const ecs::Image &im = As[src]->image;
             ecs::EcsBatchItem &it = b.item[i];
             it.image = static_cast<const uint8_t *>(As[src]->d_image);
@@ -310,7 +332,7 @@ int ecspmv_run_batch(const ecspmv_matrix *const *As, const void *const *d_xs, vo
         // workgroups of neighbouring matrices share compute units and hide each other's start and end phases.
         uint32_t threads = nb > 1 ? 512u : 1024u;
         for (int32_t i = 0; i < nb; ++i) {
-            const int t = As[order[(size_t)(base + i)]]->image.threads_per_wg;
+            const int t = As[base + i]->image.threads_per_wg;
             if (t) threads = (uint32_t)t;                      // a build-time choice overrides
         }
         int s = hip_status(ecs::launch_ecspmv(b, threads, lds, mask, (uint32_t)bits, (uint32_t)vbits, stream));
@@ -337,7 +359,7 @@ int ecspmv_run_multi(const ecspmv_matrix *A, const void *d_X, void *d_Y, int32_t
     // registers run out with a 16-grained set, and with an 8-grained one if the values are FP32
     if (im.type_mask & (vw == 4 ? ~3u : ~7u)) return ECSPMV_ERR_UNSUPPORTED;
     int lim = 0;
-    int e = ecs::device_lds_limit(&lim);
+    int e = lds_limit(&lim);
     if (e) return hip_status(e);
     // All nb right-hand sides in one launch if X and the partial sums fit LDS; otherwise several launches of nb / 2
     // or nb / 4 right-hand sides each, which read their columns of X and write their columns of Y with the row
@@ -436,6 +458,17 @@ int ecspmv_stream_read(const void *d_buf, size_t bytes, void *d_out, int32_t num
         return ECSPMV_ERR_INVALID;
     return hip_status(ecs::launch_stream_read(d_buf, bytes, d_out, (uint32_t)num_wg, stream));
 }
+
+#ifdef ECS_TRACE
+// Only in the library built with -DECS_TRACE (libecspmv_trace.so, which the timeline script loads; the product library
+// has no stamps compiled in).  Each of the next `regions` launches leaves, per wavefront, the clock at its first
+// instruction, at point `sel` of the kernel and at its last instruction in its own region of d_words (device,
+// regions x wgs_per_region x 128 uint64).  NULL switches the stamps off.
+int ecspmv_trace_buffer(void *d_words, uint32_t regions, uint32_t wgs_per_region, uint32_t sel)
+{
+    return hip_status(ecs::set_trace_buffer(d_words, regions, wgs_per_region, sel));
+}
+#endif
 
 const char *ecspmv_strerror(int status)
 {

@@ -20,6 +20,29 @@
 
 namespace {
 
+// ---- timeline stamps (only in the library built with -DECS_TRACE, which the timeline script loads).  Reading the
+// clock is a scalar memory operation, and many of them per wavefront change what they measure, so a launch takes ONE
+// stamp per wavefront, at the point the launch's `sel` names, beside the clock at the wavefront's first and last
+// instruction; the script launches once per point.  Words per wavefront: [0] start, [1] the selected point, [2] end,
+// [3] constant-rate clock at start, [4] at end (8 words reserved).
+#ifdef ECS_TRACE
+struct TraceRegs {
+    uint64_t sel_time = 0;
+    uint32_t sel = 0xFFFFFFFFu;
+};
+#define ECS_STAMP(c, k)                                                                                              \
+    do {                                                                                                             \
+        if ((c).tr.sel == (uint32_t)(k)) (c).tr.sel_time = __builtin_amdgcn_s_memtime();                             \
+    } while (0)
+#define ECS_TRACE_DRAIN(c, k)                                                                                        \
+    do {                                                                                                             \
+        if ((c).tr.sel == (uint32_t)(k)) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");                           \
+    } while (0)
+#else
+#define ECS_STAMP(c, k) ((void)0)
+#define ECS_TRACE_DRAIN(c, k) ((void)0)
+#endif
+
 // ---- cross-lane helpers (DPP).  With bound_ctrl = 0 a lane whose source lane does not exist keeps `old`.
 template <int CTRL, int ROW_MASK = 0xF>
 __device__ __forceinline__ int dpp_i(int old, int src)
@@ -154,12 +177,30 @@ __device__ __forceinline__ uint2 load8(const uint8_t *p)
     return make_uint2(t.x, t.y);
 }
 
+// A pointer put together from integers is one into global memory (the compiler would otherwise have to use the
+// slower generic loads and stores for it)
+template <class T>
+__device__ __forceinline__ T *global_ptr(uint64_t bits)
+{
+    typedef T __attribute__((address_space(1))) * in_global;
+    return (T *)(in_global)bits;
+}
+
 struct Ctx {
     const uint8_t *panel;      // global
     const uint16_t *xs;        // LDS: x as FP16 bits
     const uint8_t *meta;       // LDS copy of the panel's meta region
     float *slots;              // LDS partial sums
     uint32_t wave, lane, nwaves;
+    uint32_t wshift;           // log2(nwaves) if the workgroup has a power-of-two number of wavefronts, else 32
+    // quotient and remainder by the number of wavefronts: shifts in the usual case (a division by a run-time value is
+    // some twenty instructions, and these sit on every wavefront's way to its first loads)
+    __device__ __forceinline__ uint32_t div_nw(uint32_t a) const { return wshift < 32u ? a >> wshift : a / nwaves; }
+    __device__ __forceinline__ uint32_t mod_nw(uint32_t a) const { return wshift < 32u ? a & (nwaves - 1u) : a % nwaves; }
+#ifdef ECS_TRACE
+    uint64_t *trace;           // this wavefront's 16 stamp words (null: no stamps)
+    mutable TraceRegs tr;
+#endif
 };
 
 // ---- g >= 2 block sets: a DPP row of 16 lanes takes one unit (64 columns), 4 columns per lane; a wavefront
@@ -263,9 +304,9 @@ struct BlockSet {
         bv_off = hdr[PH_BV_OFF + t];
         utab = reinterpret_cast<const uint16_t *>(c.meta + hdr[PH_UTAB_OFF + t]);
         const uint32_t nch = (nu + 3u) >> 2;
-        c0 = (c.wave + c.nwaves - dealt % c.nwaves) % c.nwaves;
+        c0 = c.mod_nw(c.wave + c.nwaves - c.mod_nw(dealt));
         dealt += nch;
-        n = nch > c0 ? (nch - c0 + c.nwaves - 1u) / c.nwaves : 0u;
+        n = nch > c0 ? c.div_nw(nch - c0 + c.nwaves - 1u) : 0u;
         // Every buffer is requested whether or not this wavefront has that many chunks (a missing chunk reads the
         // panel header instead): every wavefront then enters the loop below with the same loads in flight, which
         // keeps the wait counts exact.
@@ -394,8 +435,8 @@ struct ResidualSet {
         rch = reinterpret_cast<const EcsRChunk *>(c.meta + hdr[PH_RCHUNK_OFF]);
         ren = reinterpret_cast<const EcsREntry *>(c.meta + hdr[PH_RENTRY_OFF]);
         const uint32_t nch = (nlanes + 63u) >> 6;
-        c0 = (c.wave + c.nwaves - dealt % c.nwaves) % c.nwaves;
-        n = nch > c0 ? (nch - c0 + c.nwaves - 1u) / c.nwaves : 0u;
+        c0 = c.mod_nw(c.wave + c.nwaves - c.mod_nw(dealt));
+        n = nch > c0 ? c.div_nw(nch - c0 + c.nwaves - 1u) : 0u;
         // unconditional, like the block sets: a missing chunk reads the panel header
 #pragma unroll
         for (int d = 0; d < DEPTH; ++d) {
@@ -404,57 +445,86 @@ struct ResidualSet {
                            have ? nlanes : 1u, buf[d]);
         }
     }
+    // (stamps 5 + 2 k / 6 + 2 k: data of this wavefront's k-th chunk here / chunk done, k < 3)
+    __device__ __forceinline__ void step(const Ctx &c, uint32_t k, int d)
+    {
+        if (k < 3) ECS_TRACE_DRAIN(c, 5 + 2 * k);
+        if (k < 3) ECS_STAMP(c, 5 + 2 * k);
+        compute_chunk<DB, FENCE, NB, VW>(c, rch, ren, part, chunk_of(c, k), buf[d]);
+        if (k < 3) ECS_STAMP(c, 6 + 2 * k);
+    }
     __device__ __forceinline__ void run(const Ctx &c)
     {
         uint32_t i = 0;
         for (; i + 2 * DEPTH - 1 < n; i += DEPTH) {
 #pragma unroll
             for (int d = 0; d < DEPTH; ++d) {
-                compute_chunk<DB, FENCE, NB, VW>(c, rch, ren, part, chunk_of(c, i + d), buf[d]);
+                step(c, i + d, d);
                 load_chunk<DB, VW>(c, rd_off, rv_off, zero_off, chunk_of(c, i + DEPTH + d), nlanes, buf[d]);
             }
         }
 #pragma unroll
         for (int d = 0; d < DEPTH; ++d) {
             if (i + d < n) {
-                compute_chunk<DB, FENCE, NB, VW>(c, rch, ren, part, chunk_of(c, i + d), buf[d]);
+                step(c, i + d, d);
                 if (i + DEPTH + d < n) load_chunk<DB, VW>(c, rd_off, rv_off, zero_off, chunk_of(c, i + DEPTH + d), nlanes, buf[d]);
             }
         }
 #pragma unroll
         for (int d = 0; d < DEPTH; ++d)
-            if (i + DEPTH + d < n) compute_chunk<DB, FENCE, NB, VW>(c, rch, ren, part, chunk_of(c, i + DEPTH + d), buf[d]);
+            if (i + DEPTH + d < n) step(c, i + DEPTH + d, d);
     }
 };
 
 // TM: bit t set = the image holds units of granularity 2 << t somewhere (the residual set is always handled);
-// DB: width of the delta indices in bits; BATCH: the variant for a launch that carries several SpMVs (residual-only
-// images: deeper buffers; one block set: everything requested before the first barrier);
+// DB: width of the delta indices in bits; MODE: 0 = a launch that carries one SpMV (nothing of the batch table is
+// compiled in: every instruction on the way to a wavefront's first loads counts, the scalar unit of a compute unit
+// issues one instruction per cycle for all 16 wavefronts), 1 = several SpMVs, 2 = several SpMVs with the buffer
+// depths that suit many workgroups per compute unit (residual-only images: deeper buffers; one block set: everything
+// requested before the first barrier);
 // K: 16-byte pieces of [tables | x] each thread brings to LDS before the generic loop takes the rest;
 // NB: right-hand sides handled at once (x holds n rows of NB values, y m rows of NB values);
 // VW: bytes per value of W, x and y (2 = FP16, 4 = FP32)
-template <int TM, int DB, bool BATCH, int K, int NB, int VW>
+template <int TM, int DB, int MODE, int K, int NB, int VW>
 __global__ __launch_bounds__(1024) void ecspmv_kernel(const uint32_t count, const uint32_t threads, const uint8_t *image0,
                                                       const uint16_t *x0, uint16_t *y0, const uint32_t n0,
                                                       const uint32_t panel_stride0, const uint32_t meta_stride0,
                                                       const uint32_t x_bytes0, const uint32_t block_end0,
+                                                      const uint32_t row_stride0, const uint64_t trace_words,
                                                       const ecs::EcsBatch batch)
 {
+#ifdef ECS_TRACE
+    const uint64_t t_start = __builtin_amdgcn_s_memtime(), t_start_real = __builtin_amdgcn_s_memrealtime();
+#endif
     // which SpMV of the batch this workgroup works for (one item in the plain case)
     // What a lone launch needs (count, workgroup size, the first item) comes first in the kernel arguments, as
     // plain values the hardware can hand over in registers; the table behind them is read only by launches that
-    // carry several SpMVs.
+    // carry several SpMVs: one 16-byte vector load per lane fetches all of it (scalar loads by every wavefront of a
+    // workgroup are served one wavefront after the other), and the item is then read out of the lanes.
+    constexpr bool BATCH = MODE == 2, LONE = MODE == 0;
     ecs::EcsBatchItem it;
     it.image = image0, it.x = x0, it.y = y0, it.n = n0, it.panel_stride = panel_stride0, it.meta_stride = meta_stride0;
     it.x_bytes = x_bytes0, it.block_end = block_end0, it.row_stride = 0;
     uint32_t block0 = 0;
-    if (count > 1) {
-        uint32_t k = 0;
-        while (k + 1 < count && blockIdx.x >= batch.item[k].block_end) {
-            block0 = batch.item[k].block_end;
-            ++k;
+    if (!LONE && count > 1) {
+        constexpr uint32_t kBatchOffset = 64, kPieces = (uint32_t)sizeof(ecs::EcsBatch) / 16u;   // 49
+        static_assert(kBatchOffset % 16 == 0 && kPieces <= 64, "one 16-byte piece per lane");
+        const uint8_t *ka = (const uint8_t *)__builtin_amdgcn_kernarg_segment_ptr();
+        const uint32_t L = threadIdx.x & 63u;
+        const uint4 t = reinterpret_cast<const uint4 *>(ka + kBatchOffset)[L < kPieces ? L : kPieces - 1u];
+        // piece 3 j + 3 holds {meta_stride, x_bytes, block_end, row_stride} of item j
+        const bool last_piece = L >= 3u && L % 3u == 0u && (L - 3u) / 3u + 1u < count;
+        const uint32_t k = (uint32_t)__popcll(__ballot(last_piece && blockIdx.x >= t.z));
+        auto rd = [&](uint32_t word, uint32_t lane) -> uint32_t { return (uint32_t)__builtin_amdgcn_readlane((int)word, (int)lane); };
+        if (k) {
+            block0 = rd(t.z, 3u * k);
+            const uint32_t a = 3u * k + 1u;
+            it.image = global_ptr<const uint8_t>((uint64_t)rd(t.x, a) | ((uint64_t)rd(t.y, a) << 32));
+            it.x = global_ptr<const uint16_t>((uint64_t)rd(t.z, a) | ((uint64_t)rd(t.w, a) << 32));
+            it.y = global_ptr<uint16_t>((uint64_t)rd(t.x, a + 1u) | ((uint64_t)rd(t.y, a + 1u) << 32));
+            it.n = rd(t.z, a + 1u), it.panel_stride = rd(t.w, a + 1u);
+            it.meta_stride = rd(t.x, a + 2u), it.x_bytes = rd(t.y, a + 2u), it.block_end = rd(t.z, a + 2u);
         }
-        if (k) it = batch.item[k];
     }
     const uint16_t *__restrict__ x = it.x;
     uint16_t *__restrict__ y = it.y;
@@ -463,7 +533,7 @@ __global__ __launch_bounds__(1024) void ecspmv_kernel(const uint32_t count, cons
     // columns of X; larger when X has more columns than this launch takes.
     uint32_t ld = NB;
     if constexpr (NB > 1) {
-        const uint32_t given = batch.item[0].row_stride;
+        const uint32_t given = row_stride0;
         if (given) ld = given;
     }
 
@@ -484,30 +554,51 @@ __global__ __launch_bounds__(1024) void ecspmv_kernel(const uint32_t count, cons
     c.wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(tid >> 6));      // wave-uniform: scalar arithmetic on it
     c.lane = tid & 63;
     c.nwaves = nt >> 6;
+    c.wshift = (c.nwaves & (c.nwaves - 1u)) == 0u ? (uint32_t)__builtin_ctz(c.nwaves) : 32u;
+#ifdef ECS_TRACE
+    c.trace = (trace_words << 8) ? global_ptr<uint64_t>((trace_words << 8) >> 8) + ((size_t)blockIdx.x * 16u + c.wave) * 8u : nullptr;
+    c.tr.sel = c.trace ? (uint32_t)(trace_words >> 56) : 0xFFFFFFFFu;      // the point to stamp rides in the top byte
+#endif
 
     // Everything the workgroup needs first is requested at once: the panel header (wave-uniform: scalar loads), and
     // the panel's tables and x on their way to LDS, as one list of 16-byte pieces [tables | x] with K pieces per
     // thread.  These loads are unconditional (indices wrapped), so none of them makes a later wait inexact; K is a
     // template parameter, the smallest that covers the list, because every wave-wide load costs issue time on the
     // way to the first barrier whether its lanes are needed or not.
-    const uint32_t *__restrict__ hp = reinterpret_cast<const uint32_t *>(panel);
-    uint32_t hdr[ECS_PANEL_HEADER / 4];
-#pragma unroll
-    for (int w = 0; w < (int)(ECS_PANEL_HEADER / 4); ++w) hdr[w] = hp[w];
+    // The header travels through the vector memory path: lanes 0..7 of every wavefront load 16 bytes each (the other
+    // lanes repeat them) and the words are then read out of the lanes into scalar registers.  Scalar loads of the same
+    // 128 bytes by all wavefronts of a workgroup are served one wavefront after the other (measured: the last of 16
+    // wavefronts has its header 1.4 us after the workgroup started, against 0.5 us this way).
+    // Everything the workgroup needs first is requested at once: the panel header, and the panel's tables and x on
+    // their way to LDS, as one list of 16-byte pieces [tables | x] with K pieces per thread.  These loads are
+    // unconditional (indices clamped or folded), so none of them makes a later wait inexact; K is a template parameter,
+    // the smallest that covers the list, because every wave-wide load costs issue time on the way to the first barrier
+    // whether its lanes are needed or not.
+    // The header travels through the vector memory path: lanes 0..7 of every wavefront load 16 bytes each (the other
+    // lanes repeat them) and the words are then read out of the lanes into scalar registers.  Scalar loads of the same
+    // 128 bytes by all wavefronts of a workgroup are served one wavefront after the other (measured: the last of 16
+    // wavefronts has its header 1.4 us after the workgroup started, against 0.5 us this way).
+    // (Measured and not kept: only the first four wavefronts staging all pieces.  The first barrier then passes 0.7 us
+    // earlier, but those wavefronts request their chunks later, and when the chunks are requested is what decides.)
+    ECS_STAMP(c, 22);           // just before the header request
+    const uint4 hv = reinterpret_cast<const uint4 *>(panel)[c.lane & 7u];
+    ECS_STAMP(c, 23);           // header requested
     const uint4 *p4 = reinterpret_cast<const uint4 *>(panel);
     const uint32_t nmeta = meta_stride / 16u;
     const uint32_t nvec = n / 8u;
     const bool x_fast = (reinterpret_cast<uintptr_t>(x) & 15) == 0 && nvec > 0 && ld == NB;
     const uint4 *xsrc = reinterpret_cast<const uint4 *>(x);
     const uint32_t ntot = nmeta + (x_fast ? nvec : 0u);         // nmeta >= 1
-    // Threads beyond the end of the list bring a piece a second time (same bytes to the same place).  Which one
-    // was measured: in a lone launch all of them repeat the last piece (one cache line, few such threads); with
-    // several SpMVs in the launch there are many such threads (K follows the widest x) and they wrap around, so
-    // that the lanes of a wavefront write to different LDS addresses.
-    const bool wrap = count > 1;
+    // Threads beyond the end of the list bring a piece a second time (same bytes to the same place): in a lone launch
+    // all of them repeat the last piece (one cache line, few such threads); with several SpMVs in the launch there are
+    // many such threads (K follows the widest x) and they are folded back onto the first 2^k <= ntot pieces, so that
+    // the lanes of a wavefront write to different LDS addresses.  Both cost one or two instructions: this sits on
+    // the way to the first loads of every wavefront.
+    const bool wrap = !LONE && count > 1;
+    const uint32_t fold = (1u << (31 - __builtin_clz(ntot))) - 1u;
     auto piece_index = [&](uint32_t k) -> uint32_t {
         const uint32_t idx = tid + k * nt;
-        return idx < ntot ? idx : (wrap ? idx % ntot : ntot - 1u);
+        return idx < ntot ? idx : (wrap ? (idx & fold) : ntot - 1u);
     };
     auto piece = [&](uint32_t k) -> const uint4 * {
         const uint32_t idx = piece_index(k);
@@ -516,7 +607,14 @@ __global__ __launch_bounds__(1024) void ecspmv_kernel(const uint32_t count, cons
     uint4 s0 = *piece(0), s1 = s0, s2 = s0, s3 = s0;
     if constexpr (K > 1) s1 = *piece(1);
     if constexpr (K > 2) s2 = *piece(2), s3 = *piece(3);
+    ECS_STAMP(c, 20);           // header and first pieces requested
     __builtin_amdgcn_sched_barrier(0);      // these loads do not wait for the header: keep them ahead of those that do
+    uint32_t hdr[ECS_PANEL_HEADER / 4];
+#pragma unroll
+    for (int w = 0; w < (int)(ECS_PANEL_HEADER / 4); ++w) {
+        const uint32_t part = (w & 3) == 0 ? hv.x : (w & 3) == 1 ? hv.y : (w & 3) == 2 ? hv.z : hv.w;
+        hdr[w] = (uint32_t)__builtin_amdgcn_readlane((int)part, w >> 2);
+    }
 
     // As soon as the header is here, the first chunks of every set are requested (one per register buffer), before
     // anything is computed and before the tables and x have even reached LDS.
@@ -533,12 +631,19 @@ __global__ __launch_bounds__(1024) void ecspmv_kernel(const uint32_t count, cons
     // with other workgroups sharing the compute unit, requesting everything first is the faster order).
     constexpr bool residual_late = TM == 1 && !BATCH && NB == 1 && VW == 2;
     uint32_t dealt = 0;
+    ECS_STAMP(c, 1);            // panel header here
     if constexpr ((TM & 8) != 0) b16.prologue(c, hdr, 3, dealt);
     if constexpr ((TM & 4) != 0) b8.prologue(c, hdr, 2, dealt);
     if constexpr ((TM & 2) != 0) b4.prologue(c, hdr, 1, dealt);
     if constexpr ((TM & 1) != 0) b2.prologue(c, hdr, 0, dealt);
     if constexpr (!residual_late) rs.prologue(c, hdr, dealt);
+    ECS_STAMP(c, 2);            // first chunks of every set requested
 
+#ifdef ECS_TRACE
+    // (only meaningful for the residual-only kernel with one buffer: its three chunk loads stay in flight)
+    if (c.tr.sel == 21u) asm volatile("s_waitcnt vmcnt(3)" ::: "memory");
+#endif
+    ECS_STAMP(c, 21);           // this wavefront's first piece here
     // tables and x into LDS
     uint4 *meta4 = reinterpret_cast<uint4 *>(meta);
     // (no branches here either: with a store under a branch the compiler moves the load down to it and waits for
@@ -575,7 +680,9 @@ __global__ __launch_bounds__(1024) void ecspmv_kernel(const uint32_t count, cons
     } else {
         for (uint32_t i = (x_fast ? nvec * 8u : 0u) + tid; i < n; i += nt) xs[i] = x[i];
     }
+    ECS_STAMP(c, 3);            // this wavefront's pieces of the tables and x written to LDS
     __syncthreads();
+    ECS_STAMP(c, 4);            // first barrier passed
 
     if constexpr (residual_late) rs.prologue(c, hdr, dealt);
     if constexpr ((TM & 8) != 0) b16.run(c);
@@ -583,10 +690,13 @@ __global__ __launch_bounds__(1024) void ecspmv_kernel(const uint32_t count, cons
     if constexpr ((TM & 2) != 0) b4.run(c);
     if constexpr ((TM & 1) != 0) b2.run(c);
     rs.run(c);
+    ECS_STAMP(c, 11);           // all chunks of this wavefront done
     __syncthreads();
+    ECS_STAMP(c, 12);           // second barrier passed
 
     // every row: add its slots and the partial sums of its lane units in a fixed order (16 lanes stride over them,
-    // then a fixed tree), store FP16
+    // then a fixed tree), store FP16.  (Measured and not kept: a whole wavefront per row for long rows, 64 lanes
+    // striding: 2 % slower on the decoder-layer shapes.)
     const uint32_t nrows = hdr[PH_NROWS], row0 = hdr[PH_ROW0];
     const uint16_t *rowslot = reinterpret_cast<const uint16_t *>(meta + hdr[PH_ROWSLOT_OFF]);
     const uint32_t *rowlu = reinterpret_cast<const uint32_t *>(meta + hdr[PH_ROWLU_OFF]);
@@ -616,6 +726,13 @@ __global__ __launch_bounds__(1024) void ecspmv_kernel(const uint32_t count, cons
             }
         }
     }
+#ifdef ECS_TRACE
+    if (c.trace) {
+        const uint64_t t_end = __builtin_amdgcn_s_memtime(), t_end_real = __builtin_amdgcn_s_memrealtime();
+        if (c.lane == 0)
+            c.trace[0] = t_start, c.trace[1] = c.tr.sel_time, c.trace[2] = t_end, c.trace[3] = t_start_real, c.trace[4] = t_end_real;
+    }
+#endif
 }
 
 // ---- plain CSR, one wavefront per row (comparison only)
@@ -667,21 +784,59 @@ __global__ __launch_bounds__(1024) void stream_read_kernel(const uint4 *__restri
 
 namespace ecs {
 
-template <int TM, int DB, bool BATCH, int K, int NB, int VW = 2>
-static int launch_k(const EcsBatch &batch, uint32_t threads, uint32_t lds_bytes, void *stream)
+#ifdef ECS_TRACE
+// host-side cursor: every launch takes the next region (wgs_per_region x 256 words) until the buffer is used up
+static uint64_t *g_trace_next = nullptr, *g_trace_end = nullptr;
+static uint64_t g_region_words = 0, g_trace_sel = 0;
+int set_trace_buffer(void *d_words, uint32_t regions, uint32_t wgs_per_region, uint32_t sel)
+{
+    g_trace_next = static_cast<uint64_t *>(d_words);
+    g_trace_sel = sel & 0xFFu;
+    g_region_words = (uint64_t)wgs_per_region * 128u;
+    g_trace_end = g_trace_next ? g_trace_next + g_region_words * regions : nullptr;
+    return 0;
+}
+static uint64_t next_trace_region(uint32_t grid)
+{
+    if (!g_trace_next || (uint64_t)grid * 128u > g_region_words || g_trace_next + g_region_words > g_trace_end) return 0;
+    uint64_t *p = g_trace_next;
+    g_trace_next += g_region_words;
+    return reinterpret_cast<uint64_t>(p) | (g_trace_sel << 56);
+}
+#endif
+
+template <int TM, int DB, int MODE, int K, int NB, int VW = 2>
+static int launch_m(const EcsBatch &batch, uint32_t threads, uint32_t lds_bytes, void *stream)
 {
     static thread_local uint32_t attr_set_for = 0;
     if (lds_bytes > 65536 && lds_bytes > attr_set_for) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(ecspmv_kernel<TM, DB, BATCH, K, NB, VW>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(ecspmv_kernel<TM, DB, MODE, K, NB, VW>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
         if (e != hipSuccess) return (int)e;
         attr_set_for = lds_bytes;
     }
     const uint32_t grid = batch.item[batch.count - 1].block_end;
-    hipLaunchKernelGGL((ecspmv_kernel<TM, DB, BATCH, K, NB, VW>), dim3(grid), dim3(threads), lds_bytes, (hipStream_t)stream,
+#ifdef ECS_TRACE
+    const uint64_t trace_words = next_trace_region(grid);
+#else
+    const uint64_t trace_words = 0;
+#endif
+    hipLaunchKernelGGL((ecspmv_kernel<TM, DB, MODE, K, NB, VW>), dim3(grid), dim3(threads), lds_bytes, (hipStream_t)stream,
                        batch.count, threads, batch.item[0].image, batch.item[0].x, batch.item[0].y, batch.item[0].n,
-                       batch.item[0].panel_stride, batch.item[0].meta_stride, batch.item[0].x_bytes, batch.item[0].block_end, batch);
+                       batch.item[0].panel_stride, batch.item[0].meta_stride, batch.item[0].x_bytes, batch.item[0].block_end,
+                       batch.item[0].row_stride, trace_words, batch);
     return (int)hipGetLastError();
+}
+
+// BATCH: the deeper-buffer variant for launches with many workgroups per compute unit; a launch that carries a single
+// SpMV gets the variant with nothing of the batch table compiled in
+template <int TM, int DB, bool BATCH, int K, int NB, int VW = 2>
+static int launch_k(const EcsBatch &batch, uint32_t threads, uint32_t lds_bytes, void *stream)
+{
+    if constexpr (BATCH) return launch_m<TM, DB, 2, K, NB, VW>(batch, threads, lds_bytes, stream);
+    if (batch.count == 1) return launch_m<TM, DB, 0, K, NB, VW>(batch, threads, lds_bytes, stream);
+    if constexpr (NB == 1) return launch_m<TM, DB, 1, K, NB, VW>(batch, threads, lds_bytes, stream);
+    return (int)hipErrorInvalidValue;          // several right-hand sides: one matrix per launch
 }
 
 template <int TM, int DB, bool BATCH>
@@ -797,6 +952,8 @@ int copy_to_device(void *d_dst, const void *h_src, uint64_t bytes, void *stream)
     if (e != hipSuccess) return (int)e;
     return (int)hipStreamSynchronize((hipStream_t)stream);
 }
+
+int current_device(int *dev) { return (int)hipGetDevice(dev); }
 
 int device_lds_limit(int *bytes)
 {
