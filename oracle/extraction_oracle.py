@@ -15,9 +15,12 @@ leaves a choice open, the reading taken is stated at the place it is used:
     (Section 6.2: only adjacent columns within the delta range; Section 6.3.1: whole load quanta only);
   * leftover columns of a level >= 1 row that no longer form a unit fall back to the two rows it was made from.
 
-Pins (tests/test_extraction_oracle.py): hand-derived block sets for constructed matrices (a row split between two
+Pins (tests/test_extraction_oracle.py): block sets derived by hand for constructed matrices (a row split between two
 partners over two rounds as in the paper's Section 4.3 narrative, identical rows climbing every level, leftovers
-below a unit, a gap wider than the delta range, tie-breaking), and the partition invariant.
+below a unit, a gap wider than the delta range, tie-breaking, and leftovers of a block lifted to 8 rows that fall back
+two levels and complete a unit there), the worked example the paper prints (tests/golden/), and the partition
+invariant.  The library is also checked without this module (tests/test_extraction_invariants.py: the rules every
+block set obeys, and greedy matching against a brute-force search over all matchings).
 """
 from __future__ import annotations
 
@@ -113,35 +116,3 @@ def hierarchical_block_extraction(rows: Sequence[Set[int]], max_granularity: int
                 block_sets.setdefault(g, []).append((r.members, tuple(taken[u:u + unit])))
     residual = [sorted(r.cols) for r in levels[0]]
     return block_sets, residual
-
-
-def nnz_balanced_panels(row_nnz: Sequence[int], num_panels: int) -> List[int]:
-    """Row bounds of contiguous panels with about equal nnz (this library's scheduling rule, not the paper's):
-    panel p ends at the first row where the running nnz reaches (p + 1) / P of the total, taking the crossing row
-    if that lands closer; every panel owns at least one row."""
-    m = len(row_nnz)
-    P = min(num_panels, m)
-    prefix = [0]
-    for v in row_nnz:
-        prefix.append(prefix[-1] + v)
-    total = prefix[-1]
-    bounds = [0]
-    r = 0
-    for p in range(P):
-        rows_left, panels_left = m - r, P - p
-        if total == 0:
-            take = -(-rows_left // panels_left)
-        else:
-            target = total * (p + 1) / P
-            e = r
-            while e < m and prefix[e + 1] <= target:
-                e += 1
-            if e < m and prefix[e + 1] - target < target - prefix[e]:
-                e += 1
-            take = e - r
-        take = max(take, 1)
-        take = min(take, rows_left - (panels_left - 1))
-        r += take
-        bounds.append(r)
-    bounds[-1] = m
-    return bounds

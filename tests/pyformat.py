@@ -19,6 +19,20 @@ def image_header(img: np.ndarray) -> dict:
                 lds_bytes=int(w[9]), image_bytes=int(q[0]), nnz=int(q[1]), delta_bits=int(w[14]))
 
 
+def panel_bounds(img: np.ndarray) -> list:
+    """Row bounds [r_0 = 0, r_1, ..., r_P = m] of the image's panels, read from the panel headers."""
+    ih = image_header(img)
+    out = []
+    for p in range(ih["num_panels"]):
+        hdr = img[IMAGE_HEADER + p * ih["panel_stride"]: IMAGE_HEADER + p * ih["panel_stride"] + 128].view(np.uint32)
+        assert not out or out[-1] == int(hdr[PH["ROW0"]])              # panels are contiguous and in order
+        if not out:
+            out.append(int(hdr[PH["ROW0"]]))
+        out.append(int(hdr[PH["ROW0"]]) + int(hdr[PH["NROWS"]]))
+    assert out[0] == 0 and out[-1] == ih["m"]
+    return out
+
+
 def deltas_of(raw: np.ndarray, bits: int) -> np.ndarray:
     """The delta indices held in `raw` bytes: one per byte, or two per byte with the earlier one in the low nibble."""
     if bits == 8:

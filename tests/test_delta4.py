@@ -201,8 +201,7 @@ def test_encoder_matches_oracle_per_panel(cid, div):
     W = gen.make_matrix(cfg, 0)
     m = W.shape[0]
     A = E.ecspmv_build_dense(W, E.make_opts(delta_bits=4, flags=B.FLAG_KEEP_SMALL_SETS))
-    nnz = np.count_nonzero(W.view(np.uint16) & 0x7FFF, axis=1).tolist()
-    bounds = xo.nnz_balanced_panels(nnz, A.ecspmv_stats().num_panels)
+    bounds = pyformat.panel_bounds(A.ecspmv_export_image())          # the library's own panels, read from the image
     want, want_res = oracle_for_matrix(W, bounds, 8)
     assert library_block_sets(A) == want
     assert library_residual(A, m) == want_res

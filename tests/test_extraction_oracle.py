@@ -100,11 +100,47 @@ def test_partition_invariant_on_random_rows():
     assert bs.get(2) and bs.get(4)
 
 
-def test_panel_bounds_rule():
-    assert xo.nnz_balanced_panels([1] * 8, 4) == [0, 2, 4, 6, 8]
-    assert xo.nnz_balanced_panels([10, 0, 0, 0, 10, 0, 0, 0], 2) == [0, 4, 8]
-    assert xo.nnz_balanced_panels([0] * 6, 4) == [0, 2, 4, 5, 6]
-    assert xo.nnz_balanced_panels([5, 5, 5], 8) == [0, 1, 2, 3]
+def test_pin_leftovers_of_a_lifted_block_fall_back_two_levels():
+    """A fall-back that reaches down two levels and, on its way, completes a unit with columns that were waiting
+    there.  Hand derivation, with a unit of 4 columns and a delta range that admits only neighbouring columns:
+
+      rows 0, 1: columns 0..11      rows 2, 3: columns 0..7      rows 4..7: columns 2..5
+
+    Level 0 (pop order: most columns first): (0,1) share 0..11 -> three units; (2,3) share 0..7 -> two units;
+    (4,5) and (6,7) share 2..5 -> one unit each.  Nothing is left, round 2 finds nothing.
+    Level 1, rows A=(0,1){0..11}, B=(2,3){0..7}, C=(4,5){2..5}, D=(6,7){2..5}: A is popped, B is its best partner
+    (8 shared against 4) -> block AB over 0..7, A keeps 8..11; C takes D -> block CD over 2..5.
+    Level 2, rows AB{0..7}, CD{2..5}: they share 2..5 -> the 8-grained block over 2..5.  AB keeps 0,1,6,7: neither
+    0,1 nor 6,7 is a unit and 1 -> 6 exceeds the delta range, so all four fall back to A and to B.
+    Decoding level 1: A now holds 0,1,6,7 beside its own 8..11.  0,1 stand alone (gap to 6), 6,7,8,9 are four
+    neighbours -> one 2-grained unit of rows (0,1); 10,11 and 0,1 fall back to rows 0 and 1.  B holds 0,1,6,7: no
+    unit, they fall back to rows 2 and 3."""
+    rows = [set(range(12)), set(range(12)), set(range(8)), set(range(8))] + [set(range(2, 6)) for _ in range(4)]
+    bs, resid = xo.hierarchical_block_extraction(rows, max_granularity=8, unit=4, max_delta=1)
+    assert as_sets(bs) == {8: [((0, 1, 2, 3, 4, 5, 6, 7), (2, 3, 4, 5))], 2: [((0, 1), (6, 7, 8, 9))]}
+    assert resid == [[0, 1, 10, 11], [0, 1, 10, 11], [0, 1, 6, 7], [0, 1, 6, 7], [], [], [], []]
+    # with the cap on g at 4 the level-2 block does not exist and AB keeps both its units
+    bs4, resid4 = xo.hierarchical_block_extraction(rows, max_granularity=4, unit=4, max_delta=1)
+    assert as_sets(bs4) == {4: [((0, 1, 2, 3), (0, 1, 2, 3)), ((0, 1, 2, 3), (4, 5, 6, 7)), ((4, 5, 6, 7), (2, 3, 4, 5))],
+                            2: [((0, 1), (8, 9, 10, 11))]}
+    assert resid4 == [[] for _ in range(8)]
+
+
+def test_library_agrees_with_the_hand_derived_fall_back():
+    """The same matrix through the library: one hand column = 16 real columns, so four hand columns make the
+    library's unit of 64, and with 4-bit deltas (range 15) only neighbouring hand columns may follow one another."""
+    wide = lambda cs: sorted(16 * c + k for c in cs for k in range(16))
+    hand = [set(range(12)), set(range(12)), set(range(8)), set(range(8))] + [set(range(2, 6)) for _ in range(4)]
+    W = np.zeros((8, 16 * 12), dtype=np.float16)
+    for i, cs in enumerate(hand):
+        W[i, wide(cs)] = 1.0
+    A = E.ecspmv_build_dense(W, E.make_opts(max_granularity=8, delta_bits=4,
+                                            flags=B.FLAG_GLOBAL_MATCHING | B.FLAG_KEEP_SMALL_SETS))
+    assert library_block_sets(A) == {8: [((0, 1, 2, 3, 4, 5, 6, 7), tuple(wide([2, 3, 4, 5])))],
+                                     2: [((0, 1), tuple(wide([6, 7, 8, 9])))]}
+    res = library_residual(A, 8)
+    assert [res[i] for i in range(8)] == [wide(c) for c in ([0, 1, 10, 11], [0, 1, 10, 11], [0, 1, 6, 7], [0, 1, 6, 7],
+                                                            [], [], [], [])]
 
 
 # ---- parity: the library's encoder against the oracle -------------------------------------------------------
@@ -161,8 +197,8 @@ def test_encoder_matches_oracle_per_panel(cid, div, panels):
     A = E.ecspmv_build_dense(W, E.make_opts(num_panels=panels, flags=B.FLAG_KEEP_SMALL_SETS))
     P = A.ecspmv_stats().num_panels
     assert P == (panels or min(256, max(1, m // 16)))
-    nnz = np.count_nonzero(W.view(np.uint16) & 0x7FFF, axis=1).tolist()
-    bounds = xo.nnz_balanced_panels(nnz, P)
+    import pyformat
+    bounds = pyformat.panel_bounds(A.ecspmv_export_image())          # the library's own panels, read from the image
     want, want_res = oracle_for_matrix(W, bounds, 8)
     assert library_block_sets(A) == want
     assert library_residual(A, m) == want_res

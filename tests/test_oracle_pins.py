@@ -157,6 +157,18 @@ def test_pattern_triples_definition():
     assert b.tolist() == [0x3E00, 0x0001, 0xC200]
 
 
+def test_pattern_triples_f32_definition():
+    """FP32 twin, on bit patterns written out by hand: +0 and -0 are not stored; the smallest subnormal, 1.5, a
+    negative value and a NaN pattern are, with exactly the bits they came with."""
+    bits = np.array([[0x00000000, 0x3FC00000, 0x80000000, 0x00000001],
+                     [0x80000001, 0x00000000, 0xC0400000, 0x7FC00001]], dtype=np.uint32)
+    r, c, b = orc.pattern_triples_f32(bits.view(np.float32))
+    assert r.tolist() == [0, 0, 1, 1, 1] and c.tolist() == [1, 3, 0, 2, 3]
+    assert b.dtype == np.uint32 and b.tolist() == [0x3FC00000, 0x00000001, 0x80000001, 0xC0400000, 0x7FC00001]
+    # and the values behind three of them, to tie the bit patterns to numbers
+    assert np.array([0x3FC00000, 0xC0400000, 0x00000001], dtype=np.uint32).view(np.float32).tolist() == [1.5, -3.0, 2.0 ** -149]
+
+
 def test_band_helper():
     ok, ratio = orc.within_band(np.array([1.0, 2.0]), np.array([1.0, 2.001]), np.array([1.0, 1.0]))
     assert ok and 0.49 < ratio < 0.51
