@@ -16,6 +16,12 @@ Beside the headline figures the default run adds, as further keys of the same li
 (`per_step_us`), one matrix hot in cache, the plain-read ceiling, the plain CSR kernel, the other delta width, several
 right-hand sides, FP32 values, and the other workload configs (`other_configs`, each in a child process).
 
+`ablation` (default run): the shape of the paper's Section 8.3 study on the same matrices and the same kernel: 16-bit
+absolute columns (index compression off), 8-bit and 4-bit delta indices, each without block extraction and with blocks of
+up to 2 / up to 8 rows: bytes per stored entry, entries per granularity, microseconds per step for `single` and `groups`.
+`parity_checked`: for every leg that is timed, the y (of copy 0) that the timed launches left behind, checked against the
+FP64 oracle's band after the timed regions (part of the cpu_baseline leg, which computes the oracle's y anyway).
+
 Prints ONE JSON line: whole-job effective HBM GB/s (bytes that must be read or written per SpMV: EC-CSR values,
 deltas and tables + x + y, divided by time), microseconds per SpMV, the roofline of the SpMV kernel and the CPU
 oracle's rate on the host cores as a baseline.
@@ -45,7 +51,7 @@ def parse_args():
     ap.add_argument("--config", type=int, default=3, help="workload config id (workloads/generators.py)")
     ap.add_argument("--copies", type=int, default=0, help="seeded copies in the rotation set (0 = enough for the config's cold-cache size)")
     ap.add_argument("--max-granularity", type=int, default=0)
-    ap.add_argument("--delta-bits", type=int, default=4, choices=[4, 8],
+    ap.add_argument("--delta-bits", type=int, default=4, choices=[4, 8, 16],
                     help="width of the delta indices: 4 = EC-CSR-4 (default: the smaller and faster format at the "
                          "sparsities of the configs), 8 = EC-CSR-8; the other one is timed in the extras")
     ap.add_argument("--panels", type=int, default=0)
@@ -70,6 +76,17 @@ def parse_args():
 def algorithmic_bytes(st) -> int:
     """Bytes one SpMV must move: EC-CSR values + deltas + tables, x once, y once."""
     return int(st.value_bytes + st.delta_bytes + st.meta_bytes + 2 * st.n + 2 * st.m)
+
+
+def kernel_source_sha() -> str:
+    """SHA-256 (first 16 hex digits) over the sources the SpMV kernel is built from: a stored counter reading is only
+    valid for the kernel it was taken with."""
+    import hashlib
+    h = hashlib.sha256()
+    for f in ("kernels.hip", "ecspmv_format.h", "launch.h", "encoder.cpp"):
+        with open(os.path.join(ROOT, "paper_2507_12205_amd", "csrc", f), "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()[:16]
 
 
 def main():
@@ -124,7 +141,8 @@ def main():
         m, n = W.shape
         x = gen.make_vector(n, seed=0, cid=cfg.cid, shape_id=sid, copy=copy)
         mats[copy][sid] = dict(A=A, st=st, x=torch.from_numpy(x.view(np.int16)).cuda().view(torch.float16),
-                               y=torch.empty(m, dtype=torch.float16, device="cuda"), bytes=algorithmic_bytes(st),
+                               y=torch.full((m,), float("nan"), dtype=torch.float16, device="cuda"),
+                               bytes=algorithmic_bytes(st),
                                name=cfg.shapes[sid][0], m=m, n=n)
         if copy == 0:
             keep_dense[sid] = (W, x)
@@ -133,6 +151,15 @@ def main():
     t_prep = time.time() - t_prep
     image_total = sum(e["st"].image_bytes for layer in mats for e in layer)
     layer_bytes = [sum(e["bytes"] for e in layer) for layer in mats]
+
+    # what the timed launches leave in y is kept (copy 0, on the host) and checked against the oracle at the end
+    parity_cases = []
+
+    def keep_for_parity(label, layer, dense, fp32=False):
+        torch.cuda.synchronize()
+        for sid, e in enumerate(layer):
+            W, x = dense[sid]
+            parity_cases.append(dict(label=label, name=cfg.shapes[sid][0], W=W, x=x, y=e["y"].cpu().numpy(), fp32=fp32))
 
     def group_of(names):
         # projections of a decoder layer that do not depend on one another share a launch
@@ -189,6 +216,7 @@ def main():
     wall = time.perf_counter() - t0
     gpu_ms = ev0.elapsed_time(ev1)
     total_ms = max(gpu_ms, 0.0) if gpu_ms > 0 else wall * 1e3
+    keep_for_parity(f"EC-CSR-{args.delta_bits} {args.launch}", mats[0], keep_dense)
     nlaunch = args.steps * nshapes
     moved = sum(layer_bytes[(args.warmup + s) % copies] for s in range(args.steps))
     value = moved / (total_ms * 1e-3) / 1e9
@@ -202,6 +230,19 @@ def main():
             classes.setdefault((e["m"], e["n"]), []).append(e)
     per_shape = {}
     for (m, n), lst in ([] if args.profile_run else classes.items()):
+        lst = list(lst)
+        # a class whose images in the rotation set do not reach 512 MB gets further seeded copies, for this timing only
+        sid0 = next(i for i, (_, m_, n_) in enumerate(cfg.shapes) if (m_, n_) == (m, n))
+        extra = copies
+        while sum(int(e["st"].image_bytes) for e in lst) <= (512 << 20) and extra < copies + 64:
+            W = gen.make_matrix(cfg, sid0, seed=0, copy=extra)
+            A = E.ecspmv_build_dense(W, opts)
+            D.upload(A, stream=stream)
+            st = A.ecspmv_stats()
+            xv = gen.make_vector(n, seed=0, cid=cfg.cid, shape_id=sid0, copy=extra)
+            lst.append(dict(A=A, st=st, x=torch.from_numpy(xv.view(np.int16)).cuda().view(torch.float16),
+                            y=torch.empty(m, dtype=torch.float16, device="cuda"), bytes=algorithmic_bytes(st)))
+            extra += 1
         tot_img = sum(int(e["st"].image_bytes) for e in lst)
         reps = max(2, (args.steps * nshapes) // (4 * len(lst)))
         for e in lst:
@@ -217,7 +258,9 @@ def main():
         us = a.elapsed_time(b) * 1e3 / (reps * len(lst))
         byt = sum(e["bytes"] for e in lst) / len(lst)
         per_shape[f"{m}x{n}"] = dict(us=round(us, 3), gbps=round(byt / us / 1e3, 1), bytes=int(byt),
-                                     cold=bool(tot_img > (300 << 20)), matrices=len(lst))
+                                     cold=bool(tot_img > (512 << 20)), matrices=len(lst),
+                                     rotation_mib=round(tot_img / 2**20))
+        del lst
     # kernel launches of the timed region in the chosen launch mode
     launches_per_step = {"single": nshapes, "groups": len(batched["groups"][0]), "all": 1}[args.launch]
     n_ev = args.steps * launches_per_step
@@ -227,14 +270,17 @@ def main():
 
     # HBM traffic per launch as counted by rocprofv3 (FETCH_SIZE + WRITE_SIZE runs, see profiles/): measured in
     # separate profiler runs of this same command, so it is read from the committed summary, not sampled here
-    traffic = None
+    traffic, traffic_stale = None, None
     tpath = os.path.join(ROOT, "profiles", "ecspmv_kernel_config3_hbm_traffic.json")
     default_build = not (args.max_granularity or args.panels or args.threads_per_wg or args.delta_bits != 4)
     if args.config == 3 and default_build and os.path.exists(tpath):
         with open(tpath) as f:
             tj = json.load(f)
-        traffic = {"single": tj.get("traffic_bytes_per_launch"),
-                   "all": tj.get("traffic_bytes_per_step_launch_all")}.get(args.launch)
+        # the counters were read from a particular build of the kernel: the figure is passed on only for that build
+        traffic_stale = tj.get("kernel_source_sha16") != kernel_source_sha()
+        if not traffic_stale:
+            traffic = {"single": tj.get("traffic_bytes_per_launch"),
+                       "all": tj.get("traffic_bytes_per_step_launch_all")}.get(args.launch)
 
     out = {
         "metric": "effective HBM GB/s of cold-cache EC-CSR SpMV (EC-CSR bytes + x + y per SpMV / time)",
@@ -250,7 +296,7 @@ def main():
         "us_per_spmv": round(us_per_spmv, 3),
         "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
+                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic, "traffic_stale": traffic_stale,
                      "kernel": "ecspmv_kernel", "avg_launch_us": round(avg_launch_us, 3),
                      "bytes_per_launch": round(byte_sum / n_ev),
                      "timing": "HIP events on the launch stream around the whole timed region / launches (gaps included)"},
@@ -277,6 +323,8 @@ def main():
     out["launches_per_step"] = launches_per_step
     alt = {}
     for mode in (() if args.profile_run else ("single", "groups", "all")):
+        for e in mats[0]:
+            e["y"].fill_(float("nan"))
         for w in range(min(args.warmup, copies)):
             run_layer(mats[w % copies], mode)
         torch.cuda.synchronize()
@@ -286,6 +334,7 @@ def main():
         ev1.record(stream)
         torch.cuda.synchronize()
         ms = ev0.elapsed_time(ev1)
+        keep_for_parity(f"EC-CSR-{args.delta_bits} {mode}", mats[0], keep_dense)
         nl = {"single": nshapes, "groups": len(batched["groups"][0]), "all": 1}[mode]
         alt[mode] = {"launches_per_step": nl, "us_per_step": round(ms * 1e3 / args.steps, 3),
                      "us_per_spmv": round(ms * 1e3 / (args.steps * nshapes), 3),
@@ -447,6 +496,8 @@ def main():
                         e["A"].ecspmv_run(e["x"].data_ptr(), e["y"].data_ptr(), sh)
                 else:
                     obatch[layer_i].ecspmv_run_batch(sh)
+            for e in olayers[0]:
+                e["y"].fill_(float("nan"))
             for w in range(ncp):
                 go(w)
             torch.cuda.synchronize()
@@ -456,6 +507,7 @@ def main():
             ev1.record(stream)
             torch.cuda.synchronize()
             ms = ev0.elapsed_time(ev1)
+            keep_for_parity(f"EC-CSR-{other_bits} {mode}", olayers[0], keep_dense)
             mv = sum(obytes[s_ % ncp] for s_ in range(args.steps))
             res[mode] = {"us_per_step": round(ms * 1e3 / args.steps, 3), "gbps": round(mv / (ms * 1e-3) / 1e9, 1),
                          "pct_of_hbm_peak": round(100.0 * mv / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 2)}
@@ -486,15 +538,16 @@ def main():
             for copy, sid, A in ex.map(make_multi, [(c, s_) for c in range(ncp) for s_ in range(nshapes)]):
                 D.upload(A, stream=stream)
                 _, m_, n_ = cfg.shapes[sid]
-                mclasses.setdefault((m_, n_), []).append((A, A.ecspmv_stats()))
+                mclasses.setdefault((m_, n_), []).append((A, A.ecspmv_stats(), copy, sid))
         multi = {}
         for (m_, n_), lst in mclasses.items():
             row = {}
             for nb in (1, 2, 4, 8):
-                X = (torch.randn((n_, nb), device="cuda") if nb > 1 else torch.randn((n_,), device="cuda")).half()
-                Y = torch.empty((m_, nb) if nb > 1 else (m_,), dtype=torch.float16, device="cuda")
+                Xh = np.stack([gen.make_vector(n_, seed=0, cid=cfg.cid, shape_id=0, copy=100 + b) for b in range(nb)], axis=1)
+                X = torch.from_numpy(np.ascontiguousarray(Xh if nb > 1 else Xh[:, 0]).view(np.int16)).cuda().view(torch.float16)
+                Y = torch.full((m_, nb) if nb > 1 else (m_,), float("nan"), dtype=torch.float16, device="cuda")
                 try:
-                    for A, _ in lst:
+                    for A, _, _, _ in lst:
                         A.ecspmv_run_multi(X.data_ptr(), Y.data_ptr(), nb, sh)
                 except E.EcspmvError as err:
                     if err.status != E.binding.ERR_UNSUPPORTED:
@@ -505,14 +558,21 @@ def main():
                 reps = max(2, (args.steps * nshapes) // (4 * len(lst)))
                 ev0.record(stream)
                 for _ in range(reps):
-                    for A, _ in lst:
+                    for A, _, _, _ in lst:
                         A.ecspmv_run_multi(X.data_ptr(), Y.data_ptr(), nb, sh)
                 ev1.record(stream)
                 torch.cuda.synchronize()
                 us = ev0.elapsed_time(ev1) * 1e3 / (reps * len(lst))
-                byt = sum(algorithmic_bytes(st) + (nb - 1) * 2 * (n_ + m_) for _, st in lst) / len(lst)
+                # Y now holds what the last matrix of the rotation wrote: checked per column at the end
+                _, _, lcopy, lsid = lst[-1]
+                Wl = keep_dense[lsid][0] if lcopy == 0 else gen.make_matrix(cfg, lsid, seed=0, copy=lcopy)
+                Yh = Y.cpu().numpy().reshape(m_, nb)
+                for b in range(nb):
+                    parity_cases.append(dict(label=f"multi_rhs nb={nb}", name=f"{m_}x{n_} column {b}", W=Wl, x=Xh[:, b].copy(),
+                                             y=Yh[:, b].copy(), fp32=False))
+                byt = sum(algorithmic_bytes(st) + (nb - 1) * 2 * (n_ + m_) for _, st, _, _ in lst) / len(lst)
                 row[f"nb{nb}"] = {"us": round(us, 3), "gbps": round(byt / us / 1e3, 1),
-                                  "cold": bool(sum(int(st.image_bytes) for _, st in lst) > (300 << 20))}
+                                  "cold": bool(sum(int(st.image_bytes) for _, st, _, _ in lst) > (300 << 20))}
             base = row.get("nb1")
             for nb in (2, 4, 8):
                 if base and row.get(f"nb{nb}"):
@@ -538,8 +598,9 @@ def main():
             for copy, sid, A in ex.map(make_f32, [(c, s_) for c in range(ncp) for s_ in range(nshapes)]):
                 D.upload(A, stream=stream)
                 st = A.ecspmv_stats()
-                flayers[copy][sid] = dict(A=A, st=st, x=torch.randn(int(st.n), device="cuda"),
-                                          y=torch.empty(int(st.m), dtype=torch.float32, device="cuda"))
+                x32 = gen.make_vector(int(st.n), seed=0, cid=cfg.cid, shape_id=sid, copy=copy).astype(np.float32)
+                flayers[copy][sid] = dict(A=A, st=st, x=torch.from_numpy(x32).cuda(),
+                                          y=torch.full((int(st.m),), float("nan"), dtype=torch.float32, device="cuda"))
         fbatch = [E.Batch([e["A"] for e in layer], [e["x"].data_ptr() for e in layer],
                           [e["y"].data_ptr() for e in layer]) for layer in flayers]
         fbytes = [sum(int(e["st"].value_bytes + e["st"].delta_bytes + e["st"].meta_bytes + 4 * e["st"].n + 4 * e["st"].m)
@@ -552,6 +613,8 @@ def main():
                         e["A"].ecspmv_run(e["x"].data_ptr(), e["y"].data_ptr(), sh)
                 else:
                     fbatch[layer_i].ecspmv_run_batch(sh)
+            for e in flayers[0]:
+                e["y"].fill_(float("nan"))
             for w in range(ncp):
                 go(w)
             torch.cuda.synchronize()
@@ -561,6 +624,9 @@ def main():
             ev1.record(stream)
             torch.cuda.synchronize()
             ms = ev0.elapsed_time(ev1)
+            keep_for_parity(f"FP32 values {mode}", flayers[0],
+                            {sid: (keep_dense[sid][0].astype(np.float32), keep_dense[sid][1].astype(np.float32))
+                             for sid in range(nshapes)}, fp32=True)
             mv = sum(fbytes[s_ % ncp] for s_ in range(args.steps))
             res[mode] = {"us_per_step": round(ms * 1e3 / args.steps, 3), "gbps": round(mv / (ms * 1e-3) / 1e9, 1),
                          "pct_of_hbm_peak": round(100.0 * mv / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 2)}
@@ -573,6 +639,63 @@ def main():
                                   [int(sum(e["st"].nnz_by_g[k] for e in flayers[0])) for k in range(5)],
                               "by_launch_mode": res}
         del flayers, fbatch
+
+    if not args.no_extras:
+        # The shape of the paper's Section 8.3 ablation, measured on this workload with this kernel: index width
+        # (16-bit absolute columns = no index compression, 8-bit deltas, 4-bit deltas) x block extraction (none, up to
+        # 2 rows, up to 8 rows).  Cold rotation of three copies (> 512 MB of images for every variant).
+        ncp = min(copies, 3)
+        abl = []
+        for bits, mg in ((16, 1), (16, 2), (16, 8), (8, 1), (8, 2), (8, 8), (4, 1), (4, 8)):
+            aopts = E.make_opts(max_granularity=mg, delta_bits=bits)
+
+            def make_abl(job):
+                copy, sid = job
+                W = keep_dense[sid][0] if copy == 0 else gen.make_matrix(cfg, sid, seed=0, copy=copy)
+                return copy, sid, E.ecspmv_build_dense(W, aopts)
+
+            alayers = [[None] * nshapes for _ in range(ncp)]
+            with ThreadPoolExecutor(max_workers=4) as ex:
+                for copy, sid, A in ex.map(make_abl, [(c, s_) for c in range(ncp) for s_ in range(nshapes)]):
+                    D.upload(A, stream=stream)
+                    alayers[copy][sid] = dict(A=A, st=A.ecspmv_stats(), x=mats[copy][sid]["x"], y=mats[copy][sid]["y"],
+                                              name=cfg.shapes[sid][0])
+            abatch = [[E.Batch([layer[i]["A"] for i in g], [layer[i]["x"].data_ptr() for i in g],
+                               [layer[i]["y"].data_ptr() for i in g]) for g in group_of([e["name"] for e in layer])]
+                      for layer in alayers]
+            abytes = [sum(algorithmic_bytes(e["st"]) for e in layer) for layer in alayers]
+            row = {"index_bits": bits, "max_granularity": mg,
+                   "bytes_per_nnz": round(sum(e["st"].image_bytes for e in alayers[0]) / sum(e["st"].nnz for e in alayers[0]), 4),
+                   "needed_bytes_per_nnz": round(abytes[0] / sum(e["st"].nnz for e in alayers[0]), 4),
+                   "nnz_by_granularity_1_2_4_8_16": [int(sum(e["st"].nnz_by_g[k] for e in alayers[0])) for k in range(5)],
+                   "x_access_cost_per_nnz": round(sum(e["st"].x_access_cost for e in alayers[0]) / sum(e["st"].nnz for e in alayers[0]), 4)}
+            for mode in ("single", "groups"):
+                def go(layer_i):
+                    if mode == "single":
+                        for e in alayers[layer_i]:
+                            e["A"].ecspmv_run(e["x"].data_ptr(), e["y"].data_ptr(), sh)
+                    else:
+                        for b in abatch[layer_i]:
+                            b.ecspmv_run_batch(sh)
+                for e in alayers[0]:
+                    e["y"].fill_(float("nan"))
+                for w in range(ncp):
+                    go(w)
+                torch.cuda.synchronize()
+                ev0.record(stream)
+                for s_ in range(args.steps):
+                    go(s_ % ncp)
+                ev1.record(stream)
+                torch.cuda.synchronize()
+                ms = ev0.elapsed_time(ev1)
+                keep_for_parity(f"ablation index {bits} bits, g <= {mg}, {mode}", alayers[0], keep_dense)
+                mv = sum(abytes[s_ % ncp] for s_ in range(args.steps))
+                row[f"us_per_step_{mode}"] = round(ms * 1e3 / args.steps, 3)
+                row[f"pct_of_hbm_peak_{mode}"] = round(100.0 * mv / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 2)
+            abl.append(row)
+            del alayers, abatch
+        out["ablation"] = {"workload": f"config {cfg.cid}, cold rotation of {ncp} copies, the same ecspmv_kernel for every row",
+                           "rows": abl}
 
     if not args.no_extras and not args.no_other_configs:
         # the other workload configs under the same protocol (own cold rotation, the same three launch modes), each
@@ -611,6 +734,24 @@ def main():
                 _, _, cores = orc.spmv_oracle_threads(W, x)
             times.append(time.perf_counter() - t)
         tmed = float(np.median(times))
+        # the y every timed leg left behind (copy 0), against the oracle's band
+        refs, checked = {}, {}
+        for pc in parity_cases:
+            key = (id(pc["W"]), pc["x"].tobytes()[:64], pc["fp32"])
+            if key not in refs:
+                refs[key] = orc.spmv_oracle_f32(pc["W"], pc["x"]) if pc["fp32"] else orc.spmv_oracle(pc["W"], pc["x"])
+            y_ref, S = refs[key]
+            ok, ratio = orc.within_band(pc["y"], y_ref, S, 2e-3, 1e-6)
+            ok = ok and not np.isnan(pc["y"].astype(np.float64)).any()
+            c = checked.setdefault(pc["label"], {"ok": True, "worst_error_over_limit": 0.0, "vectors": 0})
+            c["ok"] = bool(c["ok"] and ok)
+            c["worst_error_over_limit"] = round(max(c["worst_error_over_limit"], ratio), 4)
+            c["vectors"] += 1
+            if not ok:
+                print(f"bench.py: PARITY FAILED for {pc['label']} / {pc['name']}: worst error / limit = {ratio}", file=sys.stderr)
+        out["parity_checked"] = {"band": "|y - y_ref| <= 2e-3 * sum_j |W_ij x_j| + 1e-6, FP64 oracle, every row of every "
+                                         "matrix of copy 0 as left by the timed launches",
+                                 "all_ok": bool(all(c["ok"] for c in checked.values())), "legs": checked}
         out["cpu_baseline"] = {"value": round(layer_bytes[0] / tmed / 1e9, 3), "unit": "GB/s", "cores": int(cores),
                                "kind": "oracle",
                                "sample": f"one step ({nshapes} dense-masked FP16 matrices of copy 0), FP64 oracle, "

@@ -70,7 +70,9 @@ int parse_opts(const ecspmv_build_opts *o, ecs::BuildParams &bp, int value_bits 
         if (o->struct_size < sizeof(uint32_t)) return ECSPMV_ERR_INVALID;
         std::memcpy(&opts, o, o->struct_size < sizeof(opts) ? o->struct_size : sizeof(opts));
     }
-    if (opts.delta_bits != 0 && opts.delta_bits != 8 && opts.delta_bits != 4) return ECSPMV_ERR_UNSUPPORTED;
+    if (opts.delta_bits != 0 && opts.delta_bits != 8 && opts.delta_bits != 4 && opts.delta_bits != 16)
+        return ECSPMV_ERR_UNSUPPORTED;
+    if (opts.delta_bits == 16 && value_bits != 16) return ECSPMV_ERR_UNSUPPORTED;      // the ablation point exists for FP16 only
     bp.delta_bits = opts.delta_bits ? opts.delta_bits : 8;
     // default cap on g: 8, and 4 for FP32 values (an 8-grained FP32 unit holds 32 value registers per lane and the
     // kernel starts to spill; larger caps can still be asked for)
@@ -356,8 +358,10 @@ int ecspmv_run_multi(const ecspmv_matrix *A, const void *d_X, void *d_Y, int32_t
     if ((reinterpret_cast<uintptr_t>(d_X) & (vw - 1u)) || (reinterpret_cast<uintptr_t>(d_Y) & (vw - 1u)))
         return ECSPMV_ERR_INVALID;
     if (!A->d_image) return ECSPMV_ERR_NOT_UPLOADED;
-    // registers run out with a 16-grained set, and with an 8-grained one if the values are FP32
+    // registers run out with a 16-grained set, and with an 8-grained one if the values are FP32; absolute 16-bit
+    // columns (index compression off) exist for one vector only
     if (im.type_mask & (vw == 4 ? ~3u : ~7u)) return ECSPMV_ERR_UNSUPPORTED;
+    if (im.delta_bits == 16) return ECSPMV_ERR_UNSUPPORTED;
     int lim = 0;
     int e = lds_limit(&lim);
     if (e) return hip_status(e);

@@ -24,6 +24,9 @@
 // Delta width (Section 6.2, EC-CSR-8 / EC-CSR-4 of Section 8.2): `delta_bits` of the image header is 8 or 4.
 // With 4 bits two deltas share a byte, the earlier one in the low nibble; a unit then has 32 delta bytes (2 per
 // lane), a lane unit 8 and a residual chunk 512; the largest delta is 15 and everything else is unchanged.
+// delta_bits = 16 switches index compression off (the first step of the paper's ablation, Section 8.3): every index is
+// the 16-bit column itself, there are no gap fillers and no prefix scan; a unit has 128 index bytes (8 per lane), a lane
+// unit 32 and a residual chunk 2048.
 #ifndef ECSPMV_FORMAT_H
 #define ECSPMV_FORMAT_H
 
@@ -35,7 +38,7 @@
 #define ECS_UNIT_COLS        64u         /* block columns per unit of a g >= 2 set */
 #define ECS_LANE_ELEMS       16u         /* residual elements per lane unit */
 #define ECS_CHUNK_LANES      64u         /* lane units per residual chunk */
-#define ECS_MAX_DELTA(bits)  ((1u << (bits)) - 1u)   /* R_P - 1 */
+#define ECS_MAX_DELTA(bits)  ((1u << (bits)) - 1u)   /* R_P - 1 (with 16 bits: no limit, columns are below 65536) */
 #define ECS_UNIT_DBYTES(bits)  (8u * (bits))        /* delta bytes of a 64-column unit */
 #define ECS_LANE_DBYTES(bits)  (2u * (bits))        /* delta bytes of a residual lane unit */
 #define ECS_CHUNK_DBYTES(bits) (128u * (bits))      /* delta bytes of a full residual chunk */

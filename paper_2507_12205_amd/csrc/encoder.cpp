@@ -365,16 +365,20 @@ inline int hist_bin(unsigned d)
     return b;
 }
 
-// delta k of an array of `bits`-wide deltas; with 4 bits the earlier delta of a byte sits in its low nibble
+// index k of an array of `bits`-wide indices: a delta with 8 or 4 bits (with 4 bits the earlier delta of a byte
+// sits in its low nibble), the column itself with 16 bits (index compression switched off)
 inline void put_delta(uint8_t *d, size_t k, int bits, uint32_t v)
 {
-    if (bits == 8)
+    if (bits == 16)
+        reinterpret_cast<uint16_t *>(d)[k] = (uint16_t)v;
+    else if (bits == 8)
         d[k] = (uint8_t)v;
     else
         d[k >> 1] = (uint8_t)((k & 1) ? ((d[k >> 1] & 0x0F) | (v << 4)) : ((d[k >> 1] & 0xF0) | v));
 }
 inline uint32_t get_delta(const uint8_t *d, size_t k, int bits)
 {
+    if (bits == 16) return reinterpret_cast<const uint16_t *>(d)[k];
     return bits == 8 ? d[k] : ((d[k >> 1] >> (4 * (k & 1))) & 0xF);
 }
 
@@ -399,7 +403,7 @@ void encode_panel(const Csr &A, int64_t row0, int nrows, PanelUnits &pu, bool re
 
     // ---- residual rows -> elements (delta, value) with gap fillers and tail padding -> lane units
     struct LaneUnit {
-        uint8_t d[ECS_LANE_ELEMS];
+        uint16_t d[ECS_LANE_ELEMS];
         uint32_t v[ECS_LANE_ELEMS];
         int row;          // panel-local
         int32_t before;   // column "before" the first element: col0 for a row's first unit (its delta is 0)
@@ -409,7 +413,7 @@ void encode_panel(const Csr &A, int64_t row0, int nrows, PanelUnits &pu, bool re
     for (int r = 0; r < nrows; ++r) {
         const std::vector<int32_t> &cols = pu.resid[r];
         if (cols.empty()) continue;
-        std::vector<uint8_t> ds;
+        std::vector<uint16_t> ds;
         std::vector<uint32_t> vs;
         int32_t cur = cols[0];
         ds.push_back(0);
@@ -417,13 +421,13 @@ void encode_panel(const Csr &A, int64_t row0, int nrows, PanelUnits &pu, bool re
         for (size_t k = 1; k < cols.size(); ++k) {
             int32_t gap = cols[k] - cur;
             while (gap > max_delta) {                    // explicit zero every R_P - 1 columns (Section 6.2)
-                ds.push_back((uint8_t)max_delta);
+                ds.push_back((uint16_t)max_delta);
                 vs.push_back(0);
                 gap -= max_delta;
                 ++img.gap_pads;
                 ++img.pad_elements;
             }
-            ds.push_back((uint8_t)gap);
+            ds.push_back((uint16_t)gap);
             vs.push_back(value_at(A, row0 + r, cols[k]));
             cur = cols[k];
             ++img.delta_hist[hist_bin((unsigned)gap)];
@@ -557,9 +561,9 @@ void encode_panel(const Csr &A, int64_t row0, int nrows, PanelUnits &pu, bool re
             ue[0] = un.cols[0];
             for (uint32_t r = 0; r < g; ++r) ue[1 + r] = (uint16_t)cursor[un.rows[r]]++;
             uint8_t *d = P + hdr[PH_BD_OFF + t] + unit_db * u;
-            put_delta(d, 0, delta_bits, 0);
+            put_delta(d, 0, delta_bits, delta_bits == 16 ? un.cols[0] : 0u);
             for (unsigned k = 1; k < ECS_UNIT_COLS; ++k)
-                put_delta(d, k, delta_bits, (uint32_t)(un.cols[k] - un.cols[k - 1]));
+                put_delta(d, k, delta_bits, delta_bits == 16 ? un.cols[k] : (uint32_t)(un.cols[k] - un.cols[k - 1]));
             for (unsigned k = 0; k < ECS_UNIT_COLS; ++k)
                 for (uint32_t r = 0; r < g; ++r) flat[k * g + r] = value_at(A, row0 + un.rows[r], un.cols[k]);
             // permutation: lane j owns flat[4*j*g, 4*(j+1)*g); its k-th 128-bit group (8 halfs or 4 floats) goes
@@ -578,7 +582,11 @@ void encode_panel(const Csr &A, int64_t row0, int nrows, PanelUnits &pu, bool re
         uint8_t *v = P + hdr[PH_RV_OFF] + 1024u * vw * c;
         for (uint32_t l = 0; l < nl; ++l) {
             const LaneUnit &lu = lanes[c * ECS_CHUNK_LANES + l];
-            for (uint32_t i = 0; i < ECS_LANE_ELEMS; ++i) put_delta(d + lane_db * l, i, delta_bits, lu.d[i]);
+            uint32_t col = (uint32_t)lu.before;                        // absolute columns where deltas are switched off
+            for (uint32_t i = 0; i < ECS_LANE_ELEMS; ++i) {
+                col += lu.d[i];
+                put_delta(d + lane_db * l, i, delta_bits, delta_bits == 16 ? col : lu.d[i]);
+            }
             for (uint32_t k = 0; k < ECS_LANE_ELEMS / ep; ++k)          // k-th 128-bit load of lane l
                 for (uint32_t i = 0; i < ep; ++i) put_val(v, ep * nl * k + ep * l + i, lu.v[ep * k + i]);
         }
@@ -807,7 +815,7 @@ int walk_image(const Image &im, Triples *tri, BlockSets *bs)
                     uint32_t rel = 0;
                     for (uint32_t c = 0; c < 4; ++c) {
                         rel += get_delta(d, 4 * j + c, bits);
-                        cols[4 * j + c] = (int32_t)(ue[0] + lane_excl + rel);
+                        cols[4 * j + c] = bits == 16 ? (int32_t)get_delta(d, 4 * j + c, bits) : (int32_t)(ue[0] + lane_excl + rel);
                     }
                     lane_excl += rel;
                 }
@@ -859,7 +867,8 @@ int walk_image(const Image &im, Triples *tri, BlockSets *bs)
                     const uint32_t val = get_val(v, ep * nl * (k / ep) + ep * l + (k % ep));
                     if ((val & absmask) == 0) continue;
                     tri->rows.push_back((int32_t)(row0 + row));
-                    tri->cols.push_back((int32_t)(e.c + excl + rel));
+                    tri->cols.push_back(bits == 16 ? (int32_t)get_delta(d + ECS_LANE_DBYTES(bits) * l, k, bits)
+                                                   : (int32_t)(e.c + excl + rel));
                     tri->vals.push_back(val);
                 }
                 excl += rel;

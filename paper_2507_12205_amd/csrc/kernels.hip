@@ -208,7 +208,7 @@ struct Ctx {
 // VW = bytes per value: 2 (FP16) or 4 (FP32)
 template <int G, int VW>
 struct UnitRegs {
-    uint32_t d;            // 4 deltas: 4 bytes, or 4 nibbles in the low half
+    uint32_t d, d_hi;      // 4 indices: 4 delta bytes, or 4 nibbles in the low half, or (d, d_hi) = 4 16-bit columns
     uint4 v[G * VW / 4];   // 4 * G values of this lane
 };
 
@@ -223,10 +223,14 @@ __device__ __forceinline__ void load_unit(const Ctx &c, uint32_t bd_off, uint32_
     // one 32-bit offset from the (wave-uniform) panel pointer per load: scalar base + vector offset addressing
     const uint32_t od = bd_off + (8u * DB) * uu + (DB / 2u) * j;
     const uint32_t ov = bv_off + (64u * VW * G) * uu + 16u * j;
-    if constexpr (DB == 8)
+    if constexpr (DB == 16) {
+        const uint2 t = load8(c.panel + od);
+        r.d = t.x, r.d_hi = t.y;
+    } else if constexpr (DB == 8) {
         r.d = load4(c.panel + od);
-    else
+    } else {
         r.d = load2(c.panel + od);
+    }
 #pragma unroll
     for (int k = 0; k < G * VW / 4; ++k) r.v[k] = load16(c.panel + (ov + 256u * k));
 }
@@ -239,15 +243,20 @@ __device__ __forceinline__ void compute_unit(const Ctx &c, const uint16_t *utab,
     const bool active = u < nu;
     const uint32_t uu = min(u, nu - 1u);
     // delta decode: local prefix over the lane's 4 columns, exclusive scan over the 16 lanes, unit base
-    uint32_t rel[4];
-    constexpr uint32_t DM = (1u << DB) - 1u;
-    rel[0] = r.d & DM;
-    rel[1] = rel[0] + ((r.d >> DB) & DM);
-    rel[2] = rel[1] + ((r.d >> (2 * DB)) & DM);
-    rel[3] = rel[2] + ((r.d >> (3 * DB)) & DM);
-    const int incl = row16_incl_scan((int)rel[3]);
+    uint32_t rel[4], start;
     const uint16_t *ue = utab + uu * (1 + G);
-    const uint32_t start = (uint32_t)ue[0] + (uint32_t)incl - rel[3];
+    if constexpr (DB == 16) {                       // the indices are the columns: nothing to add up
+        rel[0] = r.d & 0xFFFFu, rel[1] = r.d >> 16, rel[2] = r.d_hi & 0xFFFFu, rel[3] = r.d_hi >> 16;
+        start = 0;
+    } else {
+        constexpr uint32_t DM = (1u << DB) - 1u;
+        rel[0] = r.d & DM;
+        rel[1] = rel[0] + ((r.d >> DB) & DM);
+        rel[2] = rel[1] + ((r.d >> (2 * DB)) & DM);
+        rel[3] = rel[2] + ((r.d >> (3 * DB)) & DM);
+        const int incl = row16_incl_scan((int)rel[3]);
+        start = (uint32_t)ue[0] + (uint32_t)incl - rel[3];
+    }
     float xv[4][NB];
 #pragma unroll
     for (int k = 0; k < 4; ++k) gather_x<NB, VW>(c.xs, start + rel[k], xv[k]);
@@ -342,7 +351,7 @@ struct BlockSet {
 // ---- residual (1-grained) set: a wavefront takes a chunk of 64 lane units, 16 elements per lane.
 template <int DB, int VW>
 struct ChunkRegs {
-    uint32_t d[DB / 2]; // 16 deltas: 16 bytes or 16 nibbles
+    uint32_t d[DB / 2]; // 16 indices: 16 delta bytes, 16 nibbles, or 16 16-bit columns
     uint4 v[VW];        // 16 values: two or four 128-bit loads
 };
 
@@ -357,7 +366,10 @@ __device__ __forceinline__ void load_chunk(const Ctx &c, uint32_t rd_off, uint32
     const uint32_t od = active ? rd_off + (128u * DB) * ch + (2u * DB) * c.lane : zero_off;
     const uint32_t ov = active ? rv_off + (1024u * VW) * ch + 16u * c.lane : zero_off;
     const uint32_t step = active ? 16u * nl : 0u;          // from one 128-bit load of this lane to its next
-    if constexpr (DB == 8) {
+    if constexpr (DB == 16) {
+        const uint4 t = load16(c.panel + od), u = load16(c.panel + (od + (active ? 16u : 0u)));
+        r.d[0] = t.x, r.d[1] = t.y, r.d[2] = t.z, r.d[3] = t.w, r.d[4] = u.x, r.d[5] = u.y, r.d[6] = u.z, r.d[7] = u.w;
+    } else if constexpr (DB == 8) {
         const uint4 t = load16(c.panel + od);
         r.d[0] = t.x, r.d[1] = t.y, r.d[2] = t.z, r.d[3] = t.w;
     } else {
@@ -374,21 +386,27 @@ template <int DB, bool FENCE, int NB, int VW>
 __device__ __forceinline__ void compute_chunk(const Ctx &c, const EcsRChunk *rch, const EcsREntry *ren, float *part,
                                               uint32_t ch, const ChunkRegs<DB, VW> &r)
 {
-    // lane-local inclusive prefix of the 16 deltas
     uint32_t rel[16];
-    constexpr int PER = 32 / DB;                  // deltas per 32-bit word
-    uint32_t run = 0;
+    int start = 0;
+    if constexpr (DB == 16) {                       // the indices are the columns: no prefix, no scan, no segment base
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        run += (r.d[i / PER] >> (DB * (i % PER))) & ((1u << DB) - 1u);
-        rel[i] = run;
+        for (int i = 0; i < 16; ++i) rel[i] = (r.d[i / 2] >> (16 * (i % 2))) & 0xFFFFu;
+    } else {
+        // lane-local inclusive prefix of the 16 deltas
+        constexpr int PER = 32 / DB;                  // deltas per 32-bit word
+        uint32_t run = 0;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            run += (r.d[i / PER] >> (DB * (i % PER))) & ((1u << DB) - 1u);
+            rel[i] = run;
+        }
+        // wave64 prefix scan of the lane totals; the segment's entry folds base column and earlier lanes
+        const int incl = wave64_incl_scan((int)run);
+        const uint64_t mask = rch[ch].head_mask;
+        const uint64_t le = (c.lane == 63) ? ~0ull : ((2ull << c.lane) - 1ull);
+        const int seg = __popcll(mask & le) - 1;
+        start = ren[rch[ch].entry0 + seg].c + incl - (int)run;
     }
-    // wave64 prefix scan of the lane totals; the segment's entry folds base column and earlier lanes
-    const int incl = wave64_incl_scan((int)run);
-    const uint64_t mask = rch[ch].head_mask;
-    const uint64_t le = (c.lane == 63) ? ~0ull : ((2ull << c.lane) - 1ull);
-    const int seg = __popcll(mask & le) - 1;
-    const int start = ren[rch[ch].entry0 + seg].c + incl - (int)run;
     float acc[NB];
 #pragma unroll
     for (int b = 0; b < NB; ++b) acc[b] = 0.0f;
@@ -861,9 +879,13 @@ static int launch_tm(const EcsBatch &batch, uint32_t threads, uint32_t lds_bytes
                      void *stream)
 {
     // FP32 values: one variant per set mask and delta width (widest staging, lone-launch buffer depths)
-    if (value_bits == 32)
+    if (value_bits == 32) {
+        if (delta_bits == 16) return (int)hipErrorInvalidValue;
         return delta_bits == 4 ? launch_k<TM, 4, false, 4, 1, 4>(batch, threads, lds_bytes, stream)
                                : launch_k<TM, 8, false, 4, 1, 4>(batch, threads, lds_bytes, stream);
+    }
+    // index compression switched off (absolute 16-bit columns): the ablation point, one variant per set mask
+    if (delta_bits == 16) return launch_k<TM, 16, false, 4, 1>(batch, threads, lds_bytes, stream);
     // Residual-only images and images with one block set have a second variant for launches that carry several
     // SpMVs.  The residual-only one (deeper buffers) pays once more than three 512-thread workgroups per compute
     // unit are launched (measured at 2, 3 and 7 per compute unit: slower, 1 % slower, faster).
@@ -891,6 +913,7 @@ int launch_ecspmv_multi(const EcsBatch &batch, uint32_t threads, uint32_t lds_by
                         uint32_t delta_bits, uint32_t value_bits, uint32_t nb, void *stream)
 {
     const int top = (type_mask & 4) ? 7 : (type_mask & 2) ? 3 : (type_mask & 1) ? 1 : 0;
+    if (delta_bits == 16) return (int)hipErrorInvalidValue;          // the ablation point exists for one vector only
     if (value_bits == 32) {                          // FP32 values: images with 4-grained sets at most
         if (delta_bits == 4) {
             if (top == 3) return launch_nb<3, 4, 4>(batch, threads, lds_bytes, nb, stream);

@@ -34,7 +34,10 @@ def panel_bounds(img: np.ndarray) -> list:
 
 
 def deltas_of(raw: np.ndarray, bits: int) -> np.ndarray:
-    """The delta indices held in `raw` bytes: one per byte, or two per byte with the earlier one in the low nibble."""
+    """The indices held in `raw` bytes: one delta per byte, or two per byte with the earlier one in the low nibble, or
+    (bits = 16, index compression off) one 16-bit column per two bytes."""
+    if bits == 16:
+        return np.ascontiguousarray(raw).view(np.uint16).astype(np.int64)
     if bits == 8:
         return raw.astype(np.int64)
     out = np.empty(2 * len(raw), dtype=np.int64)
@@ -50,7 +53,7 @@ def walk(img: np.ndarray):
     kind 'lane':  row, cols (16,), deltas (16,), values (16,) uint16, first_of_row (bool)"""
     ih = image_header(img)
     bits = ih["delta_bits"]
-    assert bits in (4, 8)
+    assert bits in (4, 8, 16)
     udb, ldb, cdb = 8 * bits, 2 * bits, 128 * bits           # delta bytes per unit, lane unit, full residual chunk
     for p in range(ih["num_panels"]):
         P = img[IMAGE_HEADER + p * ih["panel_stride"]: IMAGE_HEADER + (p + 1) * ih["panel_stride"]]
@@ -69,7 +72,7 @@ def walk(img: np.ndarray):
             for u in range(nu):
                 ue = P[ut + 2 * (1 + g) * u: ut + 2 * (1 + g) * (u + 1)].view(np.uint16)
                 d = deltas_of(P[bd + udb * u: bd + udb * (u + 1)], bits)
-                cols = int(ue[0]) + np.cumsum(d)                       # I_k = I_0 + sum of deltas
+                cols = d if bits == 16 else int(ue[0]) + np.cumsum(d)  # I_k = I_0 + sum of deltas; 16 bits: the columns
                 raw = P[bv + 128 * g * u: bv + 128 * g * (u + 1)].view(np.uint16)
                 flat = np.empty(64 * g, dtype=np.uint16)               # undo: k-th 8-half group of lane j at k*128 + 8j
                 for j in range(16):
@@ -100,8 +103,8 @@ def walk(img: np.ndarray):
                 d = deltas_of(P[rd + cdb * c + ldb * l: rd + cdb * c + ldb * (l + 1)], bits)
                 v0 = P[rv + 2048 * c + 16 * l: rv + 2048 * c + 16 * (l + 1)].view(np.uint16)
                 v1 = P[rv + 2048 * c + 16 * nl + 16 * l: rv + 2048 * c + 16 * nl + 16 * (l + 1)].view(np.uint16)
-                cols = cc + excl + np.cumsum(d)
-                excl += int(d.sum())
+                cols = d if bits == 16 else cc + excl + np.cumsum(d)
+                excl += 0 if bits == 16 else int(d.sum())
                 assert rowlu[row_local] <= 64 * c + l < rowlu[row_local + 1]     # a row's lane units are consecutive
                 yield dict(kind="lane", panel=p, row=row0 + row_local, deltas=d, cols=cols,
                            values=np.concatenate([v0, v1]), first_of_row=(row_local != prev_row),
