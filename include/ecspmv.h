@@ -67,6 +67,15 @@ typedef struct ecspmv_build_opts {
                                              Without the flag such a set is dropped (max_granularity is halved and the
                                              matrix encoded again): every set costs the launch a pipeline stage. */
 
+#define ECSPMV_FLAG_CLUSTER_ROWS     8ull /* Before the panels are cut, bring rows that share columns together: the
+                                             multi-level aggregation of Algorithm 1 (greedy row matching, Algorithm 2)
+                                             is run over ALL rows, one matching round per level, up to groups of
+                                             max_granularity rows; panels are cut from the rows listed group by group
+                                             and y is stored through a row index table (the paper's row_indices,
+                                             Section 6.1).  Blocks whose rows lie far apart in W are found this way
+                                             (the paper matches over the whole matrix, Section 4); the price is build
+                                             time quadratic in the number of rows. */
+
 /* What ecspmv_stats reports (Section 8.2 storage study, Table 2 padding). */
 typedef struct ecspmv_stats_t {
     uint32_t struct_size;

@@ -19,6 +19,7 @@ ERR_INVALID, ERR_UNSUPPORTED, ERR_NOMEM, ERR_HIP, ERR_NOT_UPLOADED, ERR_TOO_SMAL
 FLAG_GLOBAL_MATCHING = 1
 FLAG_NO_REORDER = 2
 FLAG_KEEP_SMALL_SETS = 4
+FLAG_CLUSTER_ROWS = 8
 
 EXPORTS = (
     "ecspmv_build_dense", "ecspmv_build_csr", "ecspmv_build_dense_f32", "ecspmv_build_csr_f32", "ecspmv_destroy",

@@ -89,6 +89,7 @@ int parse_opts(const ecspmv_build_opts *o, ecs::BuildParams &bp, int value_bits 
     bp.global_matching = (opts.flags & ECSPMV_FLAG_GLOBAL_MATCHING) != 0;
     bp.reorder = (opts.flags & ECSPMV_FLAG_NO_REORDER) == 0;
     bp.keep_small_sets = (opts.flags & ECSPMV_FLAG_KEEP_SMALL_SETS) != 0;
+    bp.cluster_rows = (opts.flags & ECSPMV_FLAG_CLUSTER_ROWS) != 0;
     return ECSPMV_OK;
 }
 

@@ -7,7 +7,8 @@
 //   image  = [ImageHeader, 256 B] [panel 0] [panel 1] ... [panel P-1]        each panel `panel_stride` bytes
 //   panel  = [meta: PanelHeader + tables] [payload: deltas and values of each block set]
 //
-// A panel owns a contiguous range of output rows and is processed by one workgroup, so y needs no atomics.
+// A panel owns a set of output rows (a contiguous range, or rows brought together by similarity) and is processed by
+// one workgroup, so y needs no atomics.
 // Block sets inside a panel are kept apart by granularity (Section 6.1): g = 16, 8, 4, 2 and the 1-grained
 // residual.  The unit of a g >= 2 set is 64 block columns (16 lanes x 4 columns): one 16-bit base column,
 // 64 one-byte deltas (the first is 0, Section 6.2 worked example), 64*g FP16 values stored so that the k-th
@@ -33,7 +34,7 @@
 #include <stdint.h>
 
 #define ECS_MAGIC            0x52534345u /* "ECSR" */
-#define ECS_VERSION          2u
+#define ECS_VERSION          3u
 #define ECS_IMAGE_HEADER     256u        /* bytes before panel 0 */
 #define ECS_UNIT_COLS        64u         /* block columns per unit of a g >= 2 set */
 #define ECS_LANE_ELEMS       16u         /* residual elements per lane unit */
@@ -47,7 +48,7 @@
 /* Words (uint32) of the panel header, which occupies the first ECS_PANEL_HEADER bytes of a panel. */
 #define ECS_PANEL_HEADER     128u
 enum {
-    PH_ROW0 = 0,        /* first output row of the panel */
+    PH_ROW0 = 0,        /* output row of the panel's first row (the rows of a panel are listed at PH_ROWIDX_OFF) */
     PH_NROWS = 1,       /* rows owned */
     PH_NSLOTS = 2,      /* FP32 partial-sum slots of the block sets, one per (unit, row); a row's slots are consecutive.
                            The residual set adds one partial sum per lane unit, kept after these in LDS. */
@@ -65,7 +66,9 @@ enum {
     PH_PANEL_BYTES = 26,
     PH_META_BYTES = 27,
     PH_ROWLU_OFF = 28,  /* byte offset in panel: uint32 first residual lane unit of each row, nrows + 1 entries */
-    PH_ZERO_OFF = 29    /* byte offset in panel of 16 zero bytes (what idle lanes of the last residual chunk load) */
+    PH_ZERO_OFF = 29,   /* byte offset in panel of 16 zero bytes (what idle lanes of the last residual chunk load) */
+    PH_ROWIDX_OFF = 30  /* byte offset in panel: uint32 output row of each of the panel's rows (the paper's row_indices,
+                           Section 6.1): contiguous unless the rows were clustered before the panels were cut */
 };
 
 typedef struct EcsRChunk {

@@ -243,7 +243,7 @@ void row_matching(const std::vector<LRow> &rows, int nw, std::vector<std::pair<i
     }
 }
 
-void extract_panel(const Csr &A, int64_t row0, int nrows, int max_g, int max_rounds, int delta_bits, PanelUnits &out)
+void extract_panel(const Csr &A, const int32_t *prow, int nrows, int max_g, int max_rounds, int delta_bits, PanelUnits &out)
 {
     const int32_t max_delta = (int32_t)ECS_MAX_DELTA(delta_bits);
     const int n = (int)A.n;
@@ -254,11 +254,11 @@ void extract_panel(const Csr &A, int64_t row0, int nrows, int max_g, int max_rou
         LRow &L = levels[0][r];
         L.bits.assign(nw, 0);
         L.members.assign(1, r);
-        for (int64_t p = A.rowptr[row0 + r]; p < A.rowptr[row0 + r + 1]; ++p) {
+        for (int64_t p = A.rowptr[prow[r]]; p < A.rowptr[prow[r] + 1]; ++p) {
             int c = A.col[p];
             L.bits[c >> 6] |= 1ull << (c & 63);
         }
-        L.cnt = (int)(A.rowptr[row0 + r + 1] - A.rowptr[row0 + r]);
+        L.cnt = (int)(A.rowptr[prow[r] + 1] - A.rowptr[prow[r]]);
     }
 
     std::vector<std::pair<int, int>> pairs;
@@ -382,7 +382,7 @@ inline uint32_t get_delta(const uint8_t *d, size_t k, int bits)
     return bits == 8 ? d[k] : ((d[k >> 1] >> (4 * (k & 1))) & 0xF);
 }
 
-void encode_panel(const Csr &A, int64_t row0, int nrows, PanelUnits &pu, bool reorder, int delta_bits, PanelImage &img)
+void encode_panel(const Csr &A, const int32_t *prow, int nrows, PanelUnits &pu, bool reorder, int delta_bits, PanelImage &img)
 {
     const int32_t max_delta = (int32_t)ECS_MAX_DELTA(delta_bits);
     const uint32_t unit_db = ECS_UNIT_DBYTES(delta_bits), lane_db = ECS_LANE_DBYTES(delta_bits);
@@ -417,7 +417,7 @@ void encode_panel(const Csr &A, int64_t row0, int nrows, PanelUnits &pu, bool re
         std::vector<uint32_t> vs;
         int32_t cur = cols[0];
         ds.push_back(0);
-        vs.push_back(value_at(A, row0 + r, cols[0]));
+        vs.push_back(value_at(A, prow[r], cols[0]));
         for (size_t k = 1; k < cols.size(); ++k) {
             int32_t gap = cols[k] - cur;
             while (gap > max_delta) {                    // explicit zero every R_P - 1 columns (Section 6.2)
@@ -428,7 +428,7 @@ void encode_panel(const Csr &A, int64_t row0, int nrows, PanelUnits &pu, bool re
                 ++img.pad_elements;
             }
             ds.push_back((uint16_t)gap);
-            vs.push_back(value_at(A, row0 + r, cols[k]));
+            vs.push_back(value_at(A, prow[r], cols[k]));
             cur = cols[k];
             ++img.delta_hist[hist_bin((unsigned)gap)];
         }
@@ -504,7 +504,7 @@ void encode_panel(const Csr &A, int64_t row0, int nrows, PanelUnits &pu, bool re
     uint32_t off = ECS_PANEL_HEADER;
     uint32_t hdr[ECS_PANEL_HEADER / 4];
     std::memset(hdr, 0, sizeof(hdr));
-    hdr[PH_ROW0] = (uint32_t)row0;
+    hdr[PH_ROW0] = (uint32_t)prow[0];
     hdr[PH_NROWS] = (uint32_t)nrows;
     hdr[PH_NSLOTS] = img.nslots;
     hdr[PH_NRLANES] = nlanes;
@@ -513,6 +513,8 @@ void encode_panel(const Csr &A, int64_t row0, int nrows, PanelUnits &pu, bool re
     off = align_up(off + 2u * (uint32_t)(nrows + 1), 16);
     hdr[PH_ROWLU_OFF] = off;
     off = align_up(off + 4u * (uint32_t)(nrows + 1), 16);
+    hdr[PH_ROWIDX_OFF] = off;
+    off = align_up(off + 4u * (uint32_t)nrows, 16);
     for (int t = ECS_NUM_BTYPES - 1; t >= 0; --t) {
         const uint32_t g = 2u << t;
         hdr[PH_NUNITS + t] = (uint32_t)pu.units[t].size();
@@ -565,7 +567,7 @@ void encode_panel(const Csr &A, int64_t row0, int nrows, PanelUnits &pu, bool re
             for (unsigned k = 1; k < ECS_UNIT_COLS; ++k)
                 put_delta(d, k, delta_bits, delta_bits == 16 ? un.cols[k] : (uint32_t)(un.cols[k] - un.cols[k - 1]));
             for (unsigned k = 0; k < ECS_UNIT_COLS; ++k)
-                for (uint32_t r = 0; r < g; ++r) flat[k * g + r] = value_at(A, row0 + un.rows[r], un.cols[k]);
+                for (uint32_t r = 0; r < g; ++r) flat[k * g + r] = value_at(A, prow[un.rows[r]], un.cols[k]);
             // permutation: lane j owns flat[4*j*g, 4*(j+1)*g); its k-th 128-bit group (8 halfs or 4 floats) goes
             // to byte k*256 + 16*j of the unit
             uint8_t *v = P + hdr[PH_BV_OFF + t] + 64u * vw * g * u;
@@ -598,11 +600,98 @@ void encode_panel(const Csr &A, int64_t row0, int nrows, PanelUnits &pu, bool re
     uint16_t *rs = (uint16_t *)(P + hdr[PH_ROWSLOT_OFF]);
     for (int r = 0; r <= nrows; ++r) rs[r] = (uint16_t)rowslot[r];
     std::memcpy(P + hdr[PH_ROWLU_OFF], rowlu.data(), 4u * (size_t)(nrows + 1));
+    std::memcpy(P + hdr[PH_ROWIDX_OFF], prow, 4u * (size_t)nrows);
     if (nchunks) std::memcpy(P + hdr[PH_RCHUNK_OFF], rchunks.data(), sizeof(EcsRChunk) * nchunks);
     if (!rentries.empty()) std::memcpy(P + hdr[PH_RENTRY_OFF], rentries.data(), sizeof(EcsREntry) * rentries.size());
 }
 
 }  // namespace
+
+// ------------------------------------------------------------------------------------------------------
+// row clustering: Algorithm 2 over ALL rows, level by level, to decide which rows share a panel
+// ------------------------------------------------------------------------------------------------------
+
+// The paper matches rows over the whole matrix (Section 4: the rows of a block need not be neighbours).  Here a
+// panel owns its rows, so rows that belong together must first be brought into the same panel: the multi-level
+// aggregation of Algorithm 1 is run once over all rows with one matching round per level (greedy row matching,
+// Algorithm 2; a group stands for the columns all its members share), groups of up to `group` rows result, and the
+// rows are listed group by group.  Panels are then cut from that list and extraction proper runs inside each panel.
+// Returns the row order.
+static void cluster_rows(const Csr &A, int group, int threads, std::vector<int32_t> &order)
+{
+    const int64_t m = A.m;
+    const int nw = (int)((A.n + 63) / 64);
+    struct Grp {
+        std::vector<uint64_t> bits;
+        int cnt;
+        std::vector<int32_t> members;
+    };
+    std::vector<Grp> cur((size_t)m);
+    parallel_for(m, threads, [&](int64_t i) {
+        Grp &g = cur[(size_t)i];
+        g.bits.assign(nw, 0);
+        for (int64_t p = A.rowptr[i]; p < A.rowptr[i + 1]; ++p) g.bits[A.col[p] >> 6] |= 1ull << (A.col[p] & 63);
+        g.cnt = (int)(A.rowptr[i + 1] - A.rowptr[i]);
+        g.members.assign(1, (int32_t)i);
+    });
+    for (int size = 1; size < group && cur.size() > 1; size *= 2) {
+        const int R = (int)cur.size();
+        // every group's best partner over all others (ties: lower index), in parallel; the greedy pass below takes it
+        // if it is still free and searches again among the free ones if not
+        std::vector<int> best(R, -1), best_sim(R, 0);
+        parallel_for(R, threads, [&](int64_t a) {
+            int b_best = -1, s_best = 0;
+            for (int b = 0; b < R; ++b) {
+                if (b == a || cur[b].cnt <= s_best) continue;
+                const int sim = popcount_and(cur[a].bits.data(), cur[b].bits.data(), nw);
+                if (sim > s_best) s_best = sim, b_best = b;
+            }
+            best[a] = b_best, best_sim[a] = s_best;
+        });
+        std::vector<int> pop(R);
+        for (int i = 0; i < R; ++i) pop[i] = i;
+        std::stable_sort(pop.begin(), pop.end(), [&](int a, int b) { return cur[a].cnt > cur[b].cnt; });
+        std::vector<char> free_(R, 1);
+        std::vector<Grp> next;
+        next.reserve((size_t)R / 2 + 1);
+        std::vector<int> single;
+        for (int a : pop) {
+            if (!free_[a]) continue;
+            free_[a] = 0;
+            int b = best[a];
+            if (b < 0 || !free_[b]) {
+                b = -1;
+                int s_best = 0;
+                for (int c = 0; c < R; ++c) {
+                    if (!free_[c] || cur[c].cnt <= s_best) continue;
+                    const int sim = popcount_and(cur[a].bits.data(), cur[c].bits.data(), nw);
+                    if (sim > s_best) s_best = sim, b = c;
+                }
+            }
+            if (b < 0) {
+                single.push_back(a);
+                continue;
+            }
+            free_[b] = 0;
+            Grp g;
+            g.bits.resize(nw);
+            int cnt = 0;
+            for (int w = 0; w < nw; ++w) {
+                g.bits[w] = cur[a].bits[w] & cur[b].bits[w];
+                cnt += __builtin_popcountll(g.bits[w]);
+            }
+            g.cnt = cnt;
+            g.members = cur[a].members;
+            g.members.insert(g.members.end(), cur[b].members.begin(), cur[b].members.end());
+            next.push_back(std::move(g));
+        }
+        for (int a : single) next.push_back(std::move(cur[a]));
+        cur.swap(next);
+    }
+    order.clear();
+    order.reserve((size_t)m);
+    for (const Grp &g : cur) order.insert(order.end(), g.members.begin(), g.members.end());
+}
 
 // ------------------------------------------------------------------------------------------------------
 // build
@@ -628,8 +717,20 @@ int build_image(const Csr &A, const BuildParams &bp, Image &out)
     if (bp.global_matching) P = 1;
     P = (int)std::min<int64_t>(P, m);
 
-    // nnz-balanced contiguous row panels (Section 5: even work per processing unit): panel p ends at the
-    // first row where the running nnz reaches (p + 1) / P of the total; ties in rows for empty matrices.
+    // the order in which rows are dealt to panels: as they come, or brought together by similarity first
+    const int threads = resolve_threads(bp.num_threads);
+    std::vector<int32_t> order;
+    if (bp.cluster_rows && P > 1 && bp.max_granularity > 1) {
+        cluster_rows(A, std::max(2, bp.max_granularity), threads, order);
+    } else {
+        order.resize((size_t)m);
+        for (int64_t i = 0; i < m; ++i) order[(size_t)i] = (int32_t)i;
+    }
+    std::vector<int64_t> pre((size_t)m + 1, 0);                                // stored entries before the k-th row dealt
+    for (int64_t k = 0; k < m; ++k) pre[(size_t)k + 1] = pre[(size_t)k] + (A.rowptr[(size_t)order[(size_t)k] + 1] - A.rowptr[(size_t)order[(size_t)k]]);
+
+    // nnz-balanced panels of consecutive rows of that order (Section 5: even work per processing unit): panel p ends
+    // at the first row where the running nnz reaches (p + 1) / P of the total; ties in rows for empty matrices.
     std::vector<int64_t> bound(P + 1, 0);
     {
         int64_t r = 0;
@@ -642,9 +743,9 @@ int build_image(const Csr &A, const BuildParams &bp, Image &out)
             } else {
                 const double target = (double)nnz * (p + 1) / P;
                 int64_t e = r;
-                while (e < m && (double)A.rowptr[(size_t)e + 1] <= target) ++e;
+                while (e < m && (double)pre[(size_t)e + 1] <= target) ++e;
                 // also take the row that crosses the target if that lands closer to it
-                if (e < m && (double)A.rowptr[(size_t)e + 1] - target < target - (double)A.rowptr[(size_t)e]) ++e;
+                if (e < m && (double)pre[(size_t)e + 1] - target < target - (double)pre[(size_t)e]) ++e;
                 take = e - r;
             }
             take = std::max<int64_t>(take, 1);                               // every panel owns at least one row
@@ -654,7 +755,6 @@ int build_image(const Csr &A, const BuildParams &bp, Image &out)
         bound[P] = m;                                                        // the last panel ends at m
     }
     std::vector<PanelImage> imgs;
-    const int threads = resolve_threads(bp.num_threads);
     // Every block set the image holds costs the SpMV launch a pipeline stage of its own, so a coarsest set that holds
     // next to nothing (under 1 % of the stored entries over the whole matrix) is not worth having: the granularity
     // cap is lowered and the matrix encoded again, until the coarsest set carries weight or no extraction is left.
@@ -663,8 +763,8 @@ int build_image(const Csr &A, const BuildParams &bp, Image &out)
         parallel_for(P, threads, [&](int64_t p) {
             const int64_t r0 = bound[p], r1 = (p + 1 == P) ? m : bound[p + 1];
             PanelUnits pu;
-            extract_panel(A, r0, (int)(r1 - r0), max_g, bp.max_rounds, bp.delta_bits, pu);
-            encode_panel(A, r0, (int)(r1 - r0), pu, bp.reorder, bp.delta_bits, imgs[p]);
+            extract_panel(A, order.data() + r0, (int)(r1 - r0), max_g, bp.max_rounds, bp.delta_bits, pu);
+            encode_panel(A, order.data() + r0, (int)(r1 - r0), pu, bp.reorder, bp.delta_bits, imgs[p]);
         });
         if (bp.keep_small_sets || max_g == 1) break;
         int top = 0;                                                         // coarsest set present
@@ -800,7 +900,7 @@ int walk_image(const Image &im, Triples *tri, BlockSets *bs)
         pv.hdr = (const uint32_t *)pv.P;
         pv.nrows = pv.hdr[PH_NROWS];
         pv.rowslot = (const uint16_t *)(pv.P + pv.hdr[PH_ROWSLOT_OFF]);
-        const uint32_t row0 = pv.hdr[PH_ROW0];
+        const uint32_t *rowidx = (const uint32_t *)(pv.P + pv.hdr[PH_ROWIDX_OFF]);
         for (int t = ECS_NUM_BTYPES - 1; t >= 0; --t) {
             const uint32_t g = 2u << t, nu = pv.hdr[PH_NUNITS + t];
             const uint16_t *utab = (const uint16_t *)(pv.P + pv.hdr[PH_UTAB_OFF + t]);
@@ -826,7 +926,7 @@ int walk_image(const Image &im, Triples *tri, BlockSets *bs)
                 }
                 if (bs) {
                     bs->g.push_back((int32_t)g);
-                    for (uint32_t r = 0; r < g; ++r) bs->rows.push_back((int32_t)(row0 + rows[r]));
+                    for (uint32_t r = 0; r < g; ++r) bs->rows.push_back((int32_t)rowidx[rows[r]]);
                     for (uint32_t k = 0; k < ECS_UNIT_COLS; ++k) bs->cols.push_back(cols[k]);
                 }
                 if (tri)
@@ -837,7 +937,7 @@ int walk_image(const Image &im, Triples *tri, BlockSets *bs)
                                 const uint32_t c = f / g, r = f % g;
                                 const uint32_t val = get_val(v, k * 16 * ep + ep * j + i);
                                 if ((val & absmask) == 0) continue;
-                                tri->rows.push_back((int32_t)(row0 + rows[r]));
+                                tri->rows.push_back((int32_t)rowidx[rows[r]]);
                                 tri->cols.push_back(cols[4 * j + c]);
                                 tri->vals.push_back(val);
                             }
@@ -866,7 +966,7 @@ int walk_image(const Image &im, Triples *tri, BlockSets *bs)
                     rel += get_delta(d + ECS_LANE_DBYTES(bits) * l, k, bits);
                     const uint32_t val = get_val(v, ep * nl * (k / ep) + ep * l + (k % ep));
                     if ((val & absmask) == 0) continue;
-                    tri->rows.push_back((int32_t)(row0 + row));
+                    tri->rows.push_back((int32_t)rowidx[row]);
                     tri->cols.push_back(bits == 16 ? (int32_t)get_delta(d + ECS_LANE_DBYTES(bits) * l, k, bits)
                                                    : (int32_t)(e.c + excl + rel));
                     tri->vals.push_back(val);

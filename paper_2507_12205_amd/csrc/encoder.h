@@ -28,6 +28,7 @@ struct BuildParams {
     bool global_matching = false;
     bool reorder = true;
     bool keep_small_sets = false;
+    bool cluster_rows = false;          // bring similar rows into the same panel before the panels are cut
 };
 
 struct Image {

@@ -715,7 +715,8 @@ __global__ __launch_bounds__(1024) void ecspmv_kernel(const uint32_t count, cons
     // every row: add its slots and the partial sums of its lane units in a fixed order (16 lanes stride over them,
     // then a fixed tree), store FP16.  (Measured and not kept: a whole wavefront per row for long rows, 64 lanes
     // striding: 2 % slower on the decoder-layer shapes.)
-    const uint32_t nrows = hdr[PH_NROWS], row0 = hdr[PH_ROW0];
+    const uint32_t nrows = hdr[PH_NROWS];
+    const uint32_t *rowidx = reinterpret_cast<const uint32_t *>(meta + hdr[PH_ROWIDX_OFF]);   // the output row of each row
     const uint16_t *rowslot = reinterpret_cast<const uint16_t *>(meta + hdr[PH_ROWSLOT_OFF]);
     const uint32_t *rowlu = reinterpret_cast<const uint32_t *>(meta + hdr[PH_ROWLU_OFF]);
     const float *part = slots + hdr[PH_NSLOTS] * NB;
@@ -738,9 +739,9 @@ __global__ __launch_bounds__(1024) void ecspmv_kernel(const uint32_t count, cons
         for (int b = 0; b < NB; ++b) {
             const float t = row16_allreduce(sum[b]);
             if constexpr (VW == 2) {
-                if (j == 0) y[(row0 + r) * ld + b] = __half_as_ushort(__float2half_rn(t));
+                if (j == 0) y[rowidx[r] * ld + b] = __half_as_ushort(__float2half_rn(t));
             } else {
-                if (j == 0) reinterpret_cast<float *>(y)[(row0 + r) * ld + b] = t;
+                if (j == 0) reinterpret_cast<float *>(y)[rowidx[r] * ld + b] = t;
             }
         }
     }

@@ -8,7 +8,8 @@ import numpy as np
 
 IMAGE_HEADER = 256
 PH = dict(ROW0=0, NROWS=1, NSLOTS=2, NRLANES=3, NRENTRIES=4, ROWSLOT_OFF=5, RCHUNK_OFF=6, RENTRY_OFF=7,
-          RD_OFF=8, RV_OFF=9, NUNITS=10, UTAB_OFF=14, BD_OFF=18, BV_OFF=22, PANEL_BYTES=26, META_BYTES=27, ROWLU_OFF=28, ZERO_OFF=29)
+          RD_OFF=8, RV_OFF=9, NUNITS=10, UTAB_OFF=14, BD_OFF=18, BV_OFF=22, PANEL_BYTES=26, META_BYTES=27, ROWLU_OFF=28, ZERO_OFF=29,
+          ROWIDX_OFF=30)
 
 
 def image_header(img: np.ndarray) -> dict:
@@ -19,17 +20,28 @@ def image_header(img: np.ndarray) -> dict:
                 lds_bytes=int(w[9]), image_bytes=int(q[0]), nnz=int(q[1]), delta_bits=int(w[14]))
 
 
-def panel_bounds(img: np.ndarray) -> list:
-    """Row bounds [r_0 = 0, r_1, ..., r_P = m] of the image's panels, read from the panel headers."""
+def panel_rows(img: np.ndarray) -> list:
+    """The output rows each panel owns, in the panel's own order, read from the row index tables."""
     ih = image_header(img)
     out = []
     for p in range(ih["num_panels"]):
-        hdr = img[IMAGE_HEADER + p * ih["panel_stride"]: IMAGE_HEADER + p * ih["panel_stride"] + 128].view(np.uint32)
-        assert not out or out[-1] == int(hdr[PH["ROW0"]])              # panels are contiguous and in order
-        if not out:
-            out.append(int(hdr[PH["ROW0"]]))
-        out.append(int(hdr[PH["ROW0"]]) + int(hdr[PH["NROWS"]]))
-    assert out[0] == 0 and out[-1] == ih["m"]
+        P = img[IMAGE_HEADER + p * ih["panel_stride"]: IMAGE_HEADER + (p + 1) * ih["panel_stride"]]
+        hdr = P[:128].view(np.uint32)
+        nrows, o = int(hdr[PH["NROWS"]]), int(hdr[PH["ROWIDX_OFF"]])
+        rows = P[o:o + 4 * nrows].view(np.uint32).astype(np.int64).tolist()
+        assert rows and rows[0] == int(hdr[PH["ROW0"]])
+        out.append(rows)
+    assert sorted(r for rows in out for r in rows) == list(range(ih["m"]))      # every row is owned exactly once
+    return out
+
+
+def panel_bounds(img: np.ndarray) -> list:
+    """Row bounds [r_0 = 0, r_1, ..., r_P = m] of the image's panels (rows dealt to panels as they come)."""
+    rows = panel_rows(img)
+    out = [0]
+    for r in rows:
+        assert r == list(range(out[-1], out[-1] + len(r)))             # contiguous and in order
+        out.append(out[-1] + len(r))
     return out
 
 
@@ -58,7 +70,9 @@ def walk(img: np.ndarray):
     for p in range(ih["num_panels"]):
         P = img[IMAGE_HEADER + p * ih["panel_stride"]: IMAGE_HEADER + (p + 1) * ih["panel_stride"]]
         hdr = P[:128].view(np.uint32)
-        row0, nrows = int(hdr[PH["ROW0"]]), int(hdr[PH["NROWS"]])
+        nrows = int(hdr[PH["NROWS"]])
+        o = int(hdr[PH["ROWIDX_OFF"]])
+        rowidx = P[o:o + 4 * nrows].view(np.uint32).astype(np.int64)
         o = int(hdr[PH["ROWSLOT_OFF"]])
         rowslot = P[o:o + 2 * (nrows + 1)].view(np.uint16).astype(np.int64)
 
@@ -79,7 +93,7 @@ def walk(img: np.ndarray):
                     for k in range(g // 2):
                         flat[4 * j * g + 8 * k: 4 * j * g + 8 * k + 8] = raw[k * 128 + 8 * j: k * 128 + 8 * j + 8]
                 yield dict(kind="block", panel=p, g=g, base=int(ue[0]), deltas=d, cols=cols,
-                           rows=np.array([row0 + row_of_slot(int(s)) for s in ue[1:]]),
+                           rows=np.array([rowidx[row_of_slot(int(s))] for s in ue[1:]]),
                            slots=ue[1:].astype(np.int64), values=flat.reshape(64, g))
         nlanes = int(hdr[PH["NRLANES"]])
         rc, re_, rd, rv = (int(hdr[PH[k]]) for k in ("RCHUNK_OFF", "RENTRY_OFF", "RD_OFF", "RV_OFF"))
@@ -106,7 +120,7 @@ def walk(img: np.ndarray):
                 cols = d if bits == 16 else cc + excl + np.cumsum(d)
                 excl += 0 if bits == 16 else int(d.sum())
                 assert rowlu[row_local] <= 64 * c + l < rowlu[row_local + 1]     # a row's lane units are consecutive
-                yield dict(kind="lane", panel=p, row=row0 + row_local, deltas=d, cols=cols,
+                yield dict(kind="lane", panel=p, row=int(rowidx[row_local]), deltas=d, cols=cols,
                            values=np.concatenate([v0, v1]), first_of_row=(row_local != prev_row),
                            head=bool((mask >> l) & 1))
                 prev_row = row_local

@@ -154,16 +154,19 @@ def library_block_sets(A):
     return {k: sorted(v) for k, v in out.items()}
 
 
-def oracle_for_matrix(W, bounds, max_g):
+def oracle_for_matrix(W, bounds, max_g, panels=None):
+    """The oracle run panel by panel: `bounds` cuts contiguous panels, `panels` lists each panel's rows in its order."""
     pat = (W.view(np.uint16) & 0x7FFF) != 0
+    if panels is None:
+        panels = [list(range(r0, r1)) for r0, r1 in zip(bounds[:-1], bounds[1:])]
     blocks, resid = {}, {}
-    for r0, r1 in zip(bounds[:-1], bounds[1:]):
-        rows = [set(np.nonzero(pat[i])[0].tolist()) for i in range(r0, r1)]
+    for prow in panels:
+        rows = [set(np.nonzero(pat[i])[0].tolist()) for i in prow]
         bs, rs = xo.hierarchical_block_extraction(rows, max_granularity=max_g)
         for g, units in bs.items():
-            blocks.setdefault(g, []).extend((tuple(r0 + m for m in mem), cols) for mem, cols in units)
+            blocks.setdefault(g, []).extend((tuple(prow[m] for m in mem), cols) for mem, cols in units)
         for i, c in enumerate(rs):
-            resid[r0 + i] = c
+            resid[prow[i]] = c
     return {k: sorted(v) for k, v in blocks.items()}, resid
 
 
@@ -202,3 +205,60 @@ def test_encoder_matches_oracle_per_panel(cid, div, panels):
     want, want_res = oracle_for_matrix(W, bounds, 8)
     assert library_block_sets(A) == want
     assert library_residual(A, m) == want_res
+
+
+# ---- rows brought together before the panels are cut (ECSPMV_FLAG_CLUSTER_ROWS) ------------------------------
+
+def planted(m=512, n=2048, rho=0.1, h=16, w=256, seed=0):
+    rng = np.random.default_rng(seed)
+    W = ((rng.random((m, n)) < rho) * rng.standard_normal((m, n)) * 0.02).astype(np.float16)
+    rows = np.sort(rng.choice(m, h, replace=False))
+    cols = np.sort(rng.choice(n, w, replace=False))
+    W[np.ix_(rows, cols)] = (0.05 + 0.02 * rng.standard_normal((h, w))).astype(np.float16)
+    return W, rows, cols
+
+
+def test_a_block_on_scattered_rows_is_found_once_rows_are_clustered():
+    """One dense 16 x 256 block on rows scattered over a 512-row matrix of density 0.1.  Panels of contiguous rows hold at
+    most a row or two of it and find nothing beyond pairs; with the rows brought together first, the block's rows land
+    in the same panels and most of it comes out at granularity 8, under otherwise default options."""
+    W, rows, cols = planted()
+    plain = E.ecspmv_build_dense(W, E.make_opts(flags=B.FLAG_KEEP_SMALL_SETS))
+    assert plain.ecspmv_stats().num_panels == 32
+    assert plain.ecspmv_stats().nnz_by_g[3] == 0 and plain.ecspmv_stats().nnz_by_g[2] == 0
+    A = E.ecspmv_build_dense(W, E.make_opts(flags=B.FLAG_CLUSTER_ROWS | B.FLAG_KEEP_SMALL_SETS))
+    st = A.ecspmv_stats()
+    assert st.num_panels == 32
+    bs = library_block_sets(A)
+    S, C = set(rows.tolist()), set(cols.tolist())
+
+    def planted_cells(g):
+        return {(r, c) for rs, cs in bs.get(g, []) if set(rs) <= S for r in rs for c in cs if c in C}
+
+    # the block's rows sit in two panels of eight; more than half of it comes out 8-grained (units are 64 columns of a
+    # pair's shared columns, so what two pairs took does not always line up one level higher), three quarters of it in blocks
+    assert len(planted_cells(8)) >= 0.5 * 16 * 256
+    assert {r for rs, _ in bs.get(8, []) if set(rs) <= S for r in rs} == S
+    assert len(planted_cells(8) | planted_cells(4) | planted_cells(2)) >= 0.75 * 16 * 256
+    # the image still decodes to W, and every row is owned by exactly one panel
+    import pyformat
+    from oracle import oracle as orc
+    r, c, v = A.ecspmv_decode()
+    rr, cc, vv = orc.pattern_triples(W)
+    o = np.lexsort((c, r))
+    assert np.array_equal(r[o], rr) and np.array_equal(c[o], cc) and np.array_equal(v[o], vv)
+    owned = pyformat.panel_rows(A.ecspmv_export_image())
+    assert any(p != sorted(p) or p != list(range(p[0], p[0] + len(p))) for p in owned)      # panels are not contiguous
+
+
+@pytest.mark.parametrize("cid,div", [(1, 16), (3, 8)])
+def test_encoder_matches_oracle_per_panel_with_clustered_rows(cid, div):
+    """Whatever rows a panel is given, extraction inside it is Algorithm 1 on those rows in that order."""
+    import pyformat
+    cfg = gen.scaled(gen.config(cid), div)
+    W = gen.make_matrix(cfg, 0)
+    A = E.ecspmv_build_dense(W, E.make_opts(flags=B.FLAG_CLUSTER_ROWS | B.FLAG_KEEP_SMALL_SETS))
+    panels = pyformat.panel_rows(A.ecspmv_export_image())
+    want, want_res = oracle_for_matrix(W, None, 8, panels=panels)
+    assert library_block_sets(A) == want
+    assert library_residual(A, W.shape[0]) == want_res

@@ -337,3 +337,33 @@ def test_few_long_dense_rows(E):
     A, _ = check(E, W, x, E.make_opts(max_granularity=1), label="64 x 60000 dense")
     assert A.ecspmv_stats().num_panels > 4
     check(E, W, x, E.make_opts(max_granularity=1, delta_bits=4), label="64 x 60000 dense 4-bit")
+
+
+@pytest.mark.parametrize("bits", [8, 4, 16])
+def test_rows_clustered_before_the_panels_are_cut(E, bits):
+    """ECSPMV_FLAG_CLUSTER_ROWS: a panel owns rows from all over the matrix and y is stored through the panel's row
+    index table.  Every row of y must still be written, to its own place: oracle band on a config, a planted block on
+    scattered rows, and x = e_j returning column j bit for bit."""
+    import torch
+    flags = E.binding.FLAG_CLUSTER_ROWS | E.binding.FLAG_KEEP_SMALL_SETS
+    W, x = gen.make_case(gen.scaled(gen.config(1), 4), 0)
+    A, _ = check(E, W, x, E.make_opts(delta_bits=bits, flags=flags), label=f"clustered cfg1/div4 bits{bits}")
+    rng = np.random.default_rng(8)
+    m, n = 512, 2048
+    W = ((rng.random((m, n)) < 0.1) * rng.standard_normal((m, n)) * 0.02).astype(np.float16)
+    rows, cols = rng.choice(m, 16, replace=False), np.sort(rng.choice(n, 256, replace=False))
+    W[np.ix_(rows, cols)] = (0.05 + 0.02 * rng.standard_normal((16, 256))).astype(np.float16)
+    x = rng.standard_normal(n).astype(np.float16)
+    A, _ = check(E, W, x, E.make_opts(delta_bits=bits, flags=flags), label=f"clustered planted bits{bits}")
+    if bits != 4:
+        assert A.ecspmv_stats().nnz_by_g[3] > 0                      # the planted block came out 8-grained
+    for j in (int(cols[0]), int(cols[100]), 7, n - 1):
+        e = np.zeros(n, dtype=np.float16)
+        e[j] = 1.0
+        xd = torch.from_numpy(e.view(np.int16)).cuda().view(torch.float16)
+        yd = torch.full((m,), float("nan"), dtype=torch.float16, device="cuda")
+        E.device.run(A, xd, yd)
+        torch.cuda.synchronize()
+        want = W[:, j].view(np.uint16).copy()
+        want[(want & 0x7FFF) == 0] = 0
+        assert np.array_equal(yd.cpu().numpy().view(np.uint16), want), f"column {j}"
