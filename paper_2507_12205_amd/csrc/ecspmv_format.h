@@ -4,8 +4,8 @@
 // delta_indices / block_values.  The same information is laid out here for 64-wide wavefronts and
 // 128-bit loads:
 //
-//   image  = [ImageHeader, 256 B] [panel 0] [panel 1] ... [panel P-1]        each panel `panel_stride` bytes
-//   panel  = [meta: PanelHeader + tables] [payload: deltas and values of each block set]
+//   image  = [ImageHeader, 256 B] [panel 0] [panel 1] ... [panel P-1] [zeros]   each panel `panel_stride` bytes
+//   panel  = [meta: PanelHeader + tables] [residual chunks] [deltas and values of each block set]
 //
 // A panel owns a set of output rows (a contiguous range, or rows brought together by similarity) and is processed by
 // one workgroup, so y needs no atomics.
@@ -57,8 +57,11 @@ enum {
     PH_ROWSLOT_OFF = 5, /* byte offset in panel: uint16 first slot of each row, nrows + 1 entries */
     PH_RCHUNK_OFF = 6,  /* byte offset in panel: EcsRChunk per residual chunk */
     PH_RENTRY_OFF = 7,  /* byte offset in panel: EcsREntry per residual row segment */
-    PH_RD_OFF = 8,      /* byte offset in panel: residual deltas, 16 B (8-bit) or 8 B (4-bit) per lane unit */
-    PH_RV_OFF = 9,      /* byte offset in panel: residual values, 2 x 16 B per lane unit, chunk-wise [k][lane] */
+    PH_RD_OFF = 8,      /* byte offset in panel of residual chunk 0 */
+    PH_RV_OFF = 9,      /* bytes from one residual chunk to the next: a chunk is the deltas of its 64 lane units (16, 8
+                           or 32 B each) followed by their values, the k-th 128-bit load of lane l at k * 1024 + 16 * l.
+                           A last chunk with nl < 64 lane units is stored tightly: nl delta runs (padded to 16 bytes), then
+                           the k-th load of lane l at 16 * nl * k + 16 * l */
     PH_NUNITS = 10,     /* +t: units of granularity 2 << t */
     PH_UTAB_OFF = 14,   /* +t: byte offset in panel: per unit (1 + g) uint16 = base column, g slots */
     PH_BD_OFF = 18,     /* +t: byte offset in panel: 64 (8-bit) or 32 (4-bit) delta bytes per unit */

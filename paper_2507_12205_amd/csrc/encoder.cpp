@@ -529,6 +529,21 @@ void encode_panel(const Csr &A, const int32_t *prow, int nrows, PanelUnits &pu, 
     off += 16;
     img.meta_bytes = off;
     hdr[PH_META_BYTES] = off;
+    // Residual chunks first: a chunk = the deltas of its 64 lane units, then their values, the k-th 128-bit load of
+    // lane l at k * 1024 + 16 * l; a last chunk of nl < 64 lane units is stored tightly (nl delta runs padded to 16
+    // bytes, then the k-th load of lane l at 16 * nl * k + 16 * l).
+    const uint32_t res_off = off;                                       // a multiple of 16
+    const uint32_t chunk_bytes = ECS_CHUNK_DBYTES(delta_bits) + 1024u * vw;
+    hdr[PH_RD_OFF] = res_off;
+    hdr[PH_RV_OFF] = chunk_bytes;
+    off = res_off + chunk_bytes * nchunks;
+    {
+        const uint32_t nl_last = nchunks ? nlanes - (nchunks - 1) * ECS_CHUNK_LANES : 0;
+        if (nchunks && nl_last < ECS_CHUNK_LANES)
+            off = res_off + chunk_bytes * (nchunks - 1) + align_up(lane_db * nl_last, 16) + 16u * vw * nl_last;
+    }
+    img.delta_bytes += (int64_t)lane_db * nlanes;
+    img.value_bytes += 16ll * vw * nlanes;
     for (int t = ECS_NUM_BTYPES - 1; t >= 0; --t) {
         const uint32_t g = 2u << t;
         const uint32_t nu = (uint32_t)pu.units[t].size();
@@ -541,12 +556,6 @@ void encode_panel(const Csr &A, const int32_t *prow, int nrows, PanelUnits &pu, 
         img.units_by_g[t + 1] = nu;
         img.nnz_by_g[t + 1] = (int64_t)nu * ECS_UNIT_COLS * g;
     }
-    hdr[PH_RD_OFF] = off;
-    off = align_up(off + lane_db * nlanes, 16);
-    hdr[PH_RV_OFF] = off;
-    off += 16u * vw * nlanes;
-    img.delta_bytes += (int64_t)lane_db * nlanes;
-    img.value_bytes += 16ll * vw * nlanes;
     off = align_up(off, 256);
     hdr[PH_PANEL_BYTES] = off;
     img.bytes.assign(off, 0);
@@ -580,8 +589,10 @@ void encode_panel(const Csr &A, const int32_t *prow, int nrows, PanelUnits &pu, 
     // ---- residual set
     for (uint32_t c = 0; c < nchunks; ++c) {
         const uint32_t nl = rchunks[c].nlanes;
-        uint8_t *d = P + hdr[PH_RD_OFF] + ECS_CHUNK_DBYTES(delta_bits) * c;
-        uint8_t *v = P + hdr[PH_RV_OFF] + 1024u * vw * c;
+        const bool tight = nl < ECS_CHUNK_LANES;                                 // only ever the last chunk
+        const uint32_t stride = tight ? nl : ECS_CHUNK_LANES;
+        uint8_t *d = P + res_off + chunk_bytes * c;
+        uint8_t *v = d + (tight ? align_up(lane_db * nl, 16) : ECS_CHUNK_DBYTES(delta_bits));
         for (uint32_t l = 0; l < nl; ++l) {
             const LaneUnit &lu = lanes[c * ECS_CHUNK_LANES + l];
             uint32_t col = (uint32_t)lu.before;                        // absolute columns where deltas are switched off
@@ -590,7 +601,7 @@ void encode_panel(const Csr &A, const int32_t *prow, int nrows, PanelUnits &pu, 
                 put_delta(d + lane_db * l, i, delta_bits, delta_bits == 16 ? col : lu.d[i]);
             }
             for (uint32_t k = 0; k < ECS_LANE_ELEMS / ep; ++k)          // k-th 128-bit load of lane l
-                for (uint32_t i = 0; i < ep; ++i) put_val(v, ep * nl * k + ep * l + i, lu.v[ep * k + i]);
+                for (uint32_t i = 0; i < ep; ++i) put_val(v, ep * stride * k + ep * l + i, lu.v[ep * k + i]);
         }
     }
     for (int r = 0; r < nrows; ++r)
@@ -951,8 +962,10 @@ int walk_image(const Image &im, Triples *tri, BlockSets *bs)
         for (uint32_t c = 0; c < nchunks; ++c) {
             const uint32_t nl = std::min<uint32_t>(ECS_CHUNK_LANES, nlanes - c * ECS_CHUNK_LANES);
             if (rch[c].nlanes != nl || !(rch[c].head_mask & 1)) return -101;
-            const uint8_t *d = pv.P + pv.hdr[PH_RD_OFF] + ECS_CHUNK_DBYTES(bits) * c;
-            const uint8_t *v = pv.P + pv.hdr[PH_RV_OFF] + 1024u * vw * c;
+            const bool tight = nl < ECS_CHUNK_LANES;
+            const uint32_t stride = tight ? nl : ECS_CHUNK_LANES;
+            const uint8_t *d = pv.P + pv.hdr[PH_RD_OFF] + pv.hdr[PH_RV_OFF] * c;            // chunk c: deltas, then values
+            const uint8_t *v = d + (tight ? align_up(ECS_LANE_DBYTES(bits) * nl, 16) : ECS_CHUNK_DBYTES(bits));
             int64_t excl = 0;
             for (uint32_t l = 0; l < nl; ++l) {
                 const uint64_t below = rch[c].head_mask & ((l == 63) ? ~0ull : ((2ull << l) - 1));
@@ -964,7 +977,7 @@ int walk_image(const Image &im, Triples *tri, BlockSets *bs)
                 int64_t rel = 0;
                 for (uint32_t k = 0; k < ECS_LANE_ELEMS; ++k) {
                     rel += get_delta(d + ECS_LANE_DBYTES(bits) * l, k, bits);
-                    const uint32_t val = get_val(v, ep * nl * (k / ep) + ep * l + (k % ep));
+                    const uint32_t val = get_val(v, ep * stride * (k / ep) + ep * l + (k % ep));
                     if ((val & absmask) == 0) continue;
                     tri->rows.push_back((int32_t)rowidx[row]);
                     tri->cols.push_back(bits == 16 ? (int32_t)get_delta(d + ECS_LANE_DBYTES(bits) * l, k, bits)

@@ -355,19 +355,14 @@ struct ChunkRegs {
     uint4 v[VW];        // 16 values: two or four 128-bit loads
 };
 
-// Lanes beyond the end of the last chunk load 16 zero bytes the panel keeps for them (zero deltas, zero values), so
-// that the arithmetic needs no masking.  Unconditional, like load_unit.
+// Residual chunk `ch` of a panel sits at res_off + ch * (delta bytes + value bytes of a chunk): its deltas, then its
+// values with the k-th 128-bit load of lane l at k * 1024 + 16 * l (a last chunk of nl < 64 lane units: nl delta runs
+// padded to 16 bytes, then the k-th load of lane l at 16 * nl * k + 16 * l).
 template <int DB, int VW>
-__device__ __forceinline__ void load_chunk(const Ctx &c, uint32_t rd_off, uint32_t rv_off, uint32_t zero_off, uint32_t ch,
-                                           uint32_t nlanes, ChunkRegs<DB, VW> &r)
+__device__ __forceinline__ void issue_chunk_loads(const Ctx &c, uint32_t od, uint32_t ov, uint32_t step, ChunkRegs<DB, VW> &r)
 {
-    const uint32_t nl = min(64u, nlanes - 64u * ch);
-    const bool active = c.lane < nl;
-    const uint32_t od = active ? rd_off + (128u * DB) * ch + (2u * DB) * c.lane : zero_off;
-    const uint32_t ov = active ? rv_off + (1024u * VW) * ch + 16u * c.lane : zero_off;
-    const uint32_t step = active ? 16u * nl : 0u;          // from one 128-bit load of this lane to its next
     if constexpr (DB == 16) {
-        const uint4 t = load16(c.panel + od), u = load16(c.panel + (od + (active ? 16u : 0u)));
+        const uint4 t = load16(c.panel + od), u = load16(c.panel + (od + (step ? 16u : 0u)));
         r.d[0] = t.x, r.d[1] = t.y, r.d[2] = t.z, r.d[3] = t.w, r.d[4] = u.x, r.d[5] = u.y, r.d[6] = u.z, r.d[7] = u.w;
     } else if constexpr (DB == 8) {
         const uint4 t = load16(c.panel + od);
@@ -378,6 +373,22 @@ __device__ __forceinline__ void load_chunk(const Ctx &c, uint32_t rd_off, uint32
     }
 #pragma unroll
     for (int k = 0; k < VW; ++k) r.v[k] = load16(c.panel + (ov + step * k));
+}
+
+// Lanes beyond the end of the last chunk load 16 zero bytes the panel keeps for them (zero deltas, zero values), so
+// that the arithmetic needs no masking.  Unconditional, like load_unit.
+template <int DB, int VW>
+__device__ __forceinline__ void load_chunk(const Ctx &c, uint32_t res_off, uint32_t zero_off, uint32_t ch, uint32_t nlanes,
+                                           ChunkRegs<DB, VW> &r)
+{
+    const uint32_t nl = min(64u, nlanes - 64u * ch);
+    const bool active = c.lane < nl;
+    // a last chunk with fewer than 64 lane units is stored tightly
+    const bool tight = nl < 64u;
+    const uint32_t base = res_off + (128u * DB + 1024u * VW) * ch;
+    const uint32_t od = active ? base + (2u * DB) * c.lane : zero_off;
+    const uint32_t ov = active ? base + (tight ? ((2u * DB) * nl + 15u) / 16u * 16u : 128u * DB) + 16u * c.lane : zero_off;
+    issue_chunk_loads<DB, VW>(c, od, ov, active ? (tight ? 16u * nl : 1024u) : 0u, r);
 }
 
 // One partial sum per lane unit goes to LDS (`part`, indexed by the lane unit's position in the residual stream); a
@@ -437,7 +448,7 @@ __device__ __forceinline__ void compute_chunk(const Ctx &c, const EcsRChunk *rch
 template <int DB, int DEPTH, bool FENCE, int NB, int VW>
 struct ResidualSet {
     ChunkRegs<DB, VW> buf[DEPTH];
-    uint32_t nlanes, n, c0, rd_off, rv_off, zero_off;
+    uint32_t nlanes, n, c0, res_off, zero_off;
     const EcsRChunk *rch;
     const EcsREntry *ren;
     float *part;
@@ -446,8 +457,7 @@ struct ResidualSet {
     __device__ __forceinline__ void prologue(const Ctx &c, const uint32_t *hdr, uint32_t dealt)
     {
         nlanes = hdr[PH_NRLANES];
-        rd_off = hdr[PH_RD_OFF];
-        rv_off = hdr[PH_RV_OFF];
+        res_off = hdr[PH_RD_OFF];
         zero_off = hdr[PH_ZERO_OFF];
         part = c.slots + hdr[PH_NSLOTS] * NB;
         rch = reinterpret_cast<const EcsRChunk *>(c.meta + hdr[PH_RCHUNK_OFF]);
@@ -459,8 +469,8 @@ struct ResidualSet {
 #pragma unroll
         for (int d = 0; d < DEPTH; ++d) {
             const bool have = (uint32_t)d < n;
-            load_chunk<DB, VW>(c, have ? rd_off : 0u, have ? rv_off : 0u, have ? zero_off : 0u, have ? chunk_of(c, d) : 0u,
-                           have ? nlanes : 1u, buf[d]);
+            load_chunk<DB, VW>(c, have ? res_off : 0u, have ? zero_off : 0u, have ? chunk_of(c, d) : 0u,
+                               have ? nlanes : 1u, buf[d]);
         }
     }
     // (stamps 5 + 2 k / 6 + 2 k: data of this wavefront's k-th chunk here / chunk done, k < 3)
@@ -478,14 +488,14 @@ struct ResidualSet {
 #pragma unroll
             for (int d = 0; d < DEPTH; ++d) {
                 step(c, i + d, d);
-                load_chunk<DB, VW>(c, rd_off, rv_off, zero_off, chunk_of(c, i + DEPTH + d), nlanes, buf[d]);
+                load_chunk<DB, VW>(c, res_off, zero_off, chunk_of(c, i + DEPTH + d), nlanes, buf[d]);
             }
         }
 #pragma unroll
         for (int d = 0; d < DEPTH; ++d) {
             if (i + d < n) {
                 step(c, i + d, d);
-                if (i + DEPTH + d < n) load_chunk<DB, VW>(c, rd_off, rv_off, zero_off, chunk_of(c, i + DEPTH + d), nlanes, buf[d]);
+                if (i + DEPTH + d < n) load_chunk<DB, VW>(c, res_off, zero_off, chunk_of(c, i + DEPTH + d), nlanes, buf[d]);
             }
         }
 #pragma unroll
@@ -598,15 +608,26 @@ __global__ __launch_bounds__(1024) void ecspmv_kernel(const uint32_t count, cons
     // wavefronts has its header 1.4 us after the workgroup started, against 0.5 us this way).
     // (Measured and not kept: only the first four wavefronts staging all pieces.  The first barrier then passes 0.7 us
     // earlier, but those wavefronts request their chunks later, and when the chunks are requested is what decides.)
-    ECS_STAMP(c, 22);           // just before the header request
-    const uint4 hv = reinterpret_cast<const uint4 *>(panel)[c.lane & 7u];
-    ECS_STAMP(c, 23);           // header requested
+    // buffers per set: deeper where chunks are small and frequent, shallower where registers run out
+    constexpr bool wide = (TM & 12) != 0;
+    BlockSet<16, DB, 1, NB, VW> b16;
+    BlockSet<8, DB, 1, NB, VW> b8;
+    BlockSet<4, DB, wide ? 1 : D4, NB, VW> b4;
+    BlockSet<2, DB, wide ? 2 : D2, NB, VW> b2;
+    ResidualSet<DB, wide ? 2 : (TM == 0 && BATCH ? DR0B : DR), TM == 0 && BATCH, NB, VW> rs;
+    // A lone launch of an image with one block set requests the residual set's first chunks only after the barrier:
+    // a wavefront cannot pass the barrier before its requests are out, and with both sets requested up front the
+    // whole panel is on its way before anything is computed (measured: 3-5 % of a lone launch; with more sets, or
+    // with other workgroups sharing the compute unit, requesting everything first is the faster order).
+    constexpr bool residual_late = TM == 1 && !BATCH && NB == 1 && VW == 2;
     const uint4 *p4 = reinterpret_cast<const uint4 *>(panel);
     const uint32_t nmeta = meta_stride / 16u;
     const uint32_t nvec = n / 8u;
     const bool x_fast = (reinterpret_cast<uintptr_t>(x) & 15) == 0 && nvec > 0 && ld == NB;
     const uint4 *xsrc = reinterpret_cast<const uint4 *>(x);
     const uint32_t ntot = nmeta + (x_fast ? nvec : 0u);         // nmeta >= 1
+    uint4 *meta4 = reinterpret_cast<uint4 *>(meta);
+    uint32_t hdr[ECS_PANEL_HEADER / 4];
     // Threads beyond the end of the list bring a piece a second time (same bytes to the same place): in a lone launch
     // all of them repeat the last piece (one cache line, few such threads); with several SpMVs in the launch there are
     // many such threads (K follows the widest x) and they are folded back onto the first 2^k <= ntot pieces, so that
@@ -622,12 +643,14 @@ __global__ __launch_bounds__(1024) void ecspmv_kernel(const uint32_t count, cons
         const uint32_t idx = piece_index(k);
         return idx < nmeta ? p4 + idx : xsrc + (idx - nmeta);
     };
+    ECS_STAMP(c, 22);           // just before the header request
+    const uint4 hv = reinterpret_cast<const uint4 *>(panel)[c.lane & 7u];
+    ECS_STAMP(c, 23);           // header requested
     uint4 s0 = *piece(0), s1 = s0, s2 = s0, s3 = s0;
     if constexpr (K > 1) s1 = *piece(1);
     if constexpr (K > 2) s2 = *piece(2), s3 = *piece(3);
     ECS_STAMP(c, 20);           // header and first pieces requested
     __builtin_amdgcn_sched_barrier(0);      // these loads do not wait for the header: keep them ahead of those that do
-    uint32_t hdr[ECS_PANEL_HEADER / 4];
 #pragma unroll
     for (int w = 0; w < (int)(ECS_PANEL_HEADER / 4); ++w) {
         const uint32_t part = (w & 3) == 0 ? hv.x : (w & 3) == 1 ? hv.y : (w & 3) == 2 ? hv.z : hv.w;
@@ -636,18 +659,6 @@ __global__ __launch_bounds__(1024) void ecspmv_kernel(const uint32_t count, cons
 
     // As soon as the header is here, the first chunks of every set are requested (one per register buffer), before
     // anything is computed and before the tables and x have even reached LDS.
-    // buffers per set: deeper where chunks are small and frequent, shallower where registers run out
-    constexpr bool wide = (TM & 12) != 0;
-    BlockSet<16, DB, 1, NB, VW> b16;
-    BlockSet<8, DB, 1, NB, VW> b8;
-    BlockSet<4, DB, wide ? 1 : D4, NB, VW> b4;
-    BlockSet<2, DB, wide ? 2 : D2, NB, VW> b2;
-    ResidualSet<DB, wide ? 2 : (TM == 0 && BATCH ? DR0B : DR), TM == 0 && BATCH, NB, VW> rs;
-    // A lone launch of an image with one block set requests the residual set's first chunks only after the barrier:
-    // a wavefront cannot pass the barrier before its requests are out, and with both sets requested up front the
-    // whole panel is on its way before anything is computed (measured: 3-5 % of a lone launch; with more sets, or
-    // with other workgroups sharing the compute unit, requesting everything first is the faster order).
-    constexpr bool residual_late = TM == 1 && !BATCH && NB == 1 && VW == 2;
     uint32_t dealt = 0;
     ECS_STAMP(c, 1);            // panel header here
     if constexpr ((TM & 8) != 0) b16.prologue(c, hdr, 3, dealt);
@@ -663,7 +674,6 @@ __global__ __launch_bounds__(1024) void ecspmv_kernel(const uint32_t count, cons
 #endif
     ECS_STAMP(c, 21);           // this wavefront's first piece here
     // tables and x into LDS
-    uint4 *meta4 = reinterpret_cast<uint4 *>(meta);
     // (no branches here either: with a store under a branch the compiler moves the load down to it and waits for
     // it there)
     auto place = [&](uint32_t k) -> uint4 * {
@@ -673,6 +683,7 @@ __global__ __launch_bounds__(1024) void ecspmv_kernel(const uint32_t count, cons
     *place(0) = s0;
     if constexpr (K > 1) *place(1) = s1;
     if constexpr (K > 2) *place(2) = s2, *place(3) = s3;
+    static_assert(K <= 4, "at most four pieces per thread are brought here");
     for (uint32_t idx = tid + (uint32_t)K * nt; idx < ntot; idx += nt) {
         if (idx < nmeta)
             meta4[idx] = p4[idx];

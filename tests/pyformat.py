@@ -114,9 +114,17 @@ def walk(img: np.ndarray):
                 e = P[re_ + 8 * (entry0 + seg): re_ + 8 * (entry0 + seg + 1)]
                 cc = int(e[:4].view(np.int32)[0])
                 _, row_local = (int(v) for v in e[4:8].view(np.uint16))
-                d = deltas_of(P[rd + cdb * c + ldb * l: rd + cdb * c + ldb * (l + 1)], bits)
-                v0 = P[rv + 2048 * c + 16 * l: rv + 2048 * c + 16 * (l + 1)].view(np.uint16)
-                v1 = P[rv + 2048 * c + 16 * nl + 16 * l: rv + 2048 * c + 16 * nl + 16 * (l + 1)].view(np.uint16)
+                # chunk c sits at rd + c * rv (rv: bytes from one chunk to the next): its deltas, then its values with the
+                # k-th 128-bit load of lane l at k * 1024 + 16 * l
+                # (a last chunk with nl < 64 lane units is stored tightly: nl delta runs padded
+                # to 16 bytes, then the k-th load of lane l at 16 * nl * k + 16 * l)
+                cb = rd + rv * c
+                tight = nl < 64
+                vb = cb + ((ldb * nl + 15) // 16 * 16 if tight else cdb)
+                vs = 16 * (nl if tight else 64)
+                d = deltas_of(P[cb + ldb * l: cb + ldb * (l + 1)], bits)
+                v0 = P[vb + 16 * l: vb + 16 * (l + 1)].view(np.uint16)
+                v1 = P[vb + vs + 16 * l: vb + vs + 16 * (l + 1)].view(np.uint16)
                 cols = d if bits == 16 else cc + excl + np.cumsum(d)
                 excl += 0 if bits == 16 else int(d.sum())
                 assert rowlu[row_local] <= 64 * c + l < rowlu[row_local + 1]     # a row's lane units are consecutive
