@@ -280,6 +280,7 @@ def main():
         traffic_stale = tj.get("kernel_source_sha16") != kernel_source_sha()
         if not traffic_stale:
             traffic = {"single": tj.get("traffic_bytes_per_launch"),
+                       "groups": tj.get("traffic_bytes_per_launch_groups"),
                        "all": tj.get("traffic_bytes_per_step_launch_all")}.get(args.launch)
 
     out = {
@@ -440,6 +441,48 @@ def main():
             out["stream_read_ceiling_gbps"][f"one_launch_per_step_{nwg}wg"] = round(
                 step_bytes * reps / (ev0.elapsed_time(ev1) * 1e-3) / 1e9, 1)
         del big
+
+        # the floor under lone launches: a launch that reads nothing, and the fastest plain read found (one contiguous
+        # slice per workgroup) of as many bytes as an SpMV of each shape has to move, one launch each, cold (rotation
+        # over 640 MB of buffers); the sum over the step's shapes is what seven lone launches cannot go below
+        nul = torch.zeros(4096, dtype=torch.int32, device="cuda")
+        floor = {}
+        for nwg, thr in ((256, 1024), (512, 512)):
+            E.ecspmv_empty_launch(nul.data_ptr(), nwg, thr, 50, sh)
+            torch.cuda.synchronize()
+            ev0.record(stream)
+            E.ecspmv_empty_launch(nul.data_ptr(), nwg, thr, 1000, sh)
+            ev1.record(stream)
+            torch.cuda.synchronize()
+            floor[f"empty_launch_{nwg}x{thr}_us"] = round(ev0.elapsed_time(ev1), 3)      # ms per 1000 = us per launch
+        pool = torch.randint(0, 255, (640 << 20,), dtype=torch.uint8, device="cuda")
+        reads, step_floor = {}, 0.0
+        for (m, n), lst in classes.items():
+            nbytes = int(sum(e["bytes"] for e in lst) / len(lst)) // 256 * 256
+            nbuf = pool.numel() // nbytes
+            best = None
+            for nwg, thr in ((256, 1024), (512, 512), (1024, 512), (1024, 256), (2048, 256)):
+                for r in range(nbuf):
+                    E.ecspmv_stream_read_sliced(pool.data_ptr() + r * nbytes, nbytes, nul.data_ptr(), nwg, thr, sh)
+                torch.cuda.synchronize()
+                ev0.record(stream)
+                reps = 3 * nbuf
+                for r in range(reps):
+                    E.ecspmv_stream_read_sliced(pool.data_ptr() + (r % nbuf) * nbytes, nbytes, nul.data_ptr(), nwg, thr, sh)
+                ev1.record(stream)
+                torch.cuda.synchronize()
+                us = ev0.elapsed_time(ev1) * 1e3 / reps
+                if best is None or us < best[0]:
+                    best = (us, nwg, thr)
+            spmv_us = per_shape.get(f"{m}x{n}", {}).get("us")
+            reads[f"{m}x{n}"] = {"bytes": nbytes, "read_us": round(best[0], 3), "workgroups": best[1], "threads": best[2],
+                                 "spmv_us": spmv_us, "spmv_over_read": round(spmv_us / best[0], 3) if spmv_us else None}
+            step_floor += best[0] * sum(1 for e in mats[0] if (e["m"], e["n"]) == (m, n))
+        del pool
+        floor["plain_read_lone_launch_cold"] = reads
+        floor["step_of_lone_launches_us"] = round(step_floor, 3)
+        floor["step_of_lone_launches_pct_of_hbm_peak"] = round(100.0 * layer_bytes[0] / (step_floor * 1e-6) / 1e9 / HBM_PEAK_GBPS, 2)
+        out["launch_floor"] = floor
 
         # plain CSR kernel on the same matrices (first two copies, rotation > 512 MB of CSR data)
         csr_layers = []

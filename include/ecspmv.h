@@ -4,7 +4,7 @@
  * EC-CSR (paper, Section 6) stores a pruned FP16 weight matrix as dense g-grained blocks
  * found by hierarchical block extraction (Section 4, Algorithms 1 and 2) plus the
  * residual 1-grained rows, with 8-bit or 4-bit delta-encoded column indices (Section 6.2; EC-CSR-8 and
- * EC-CSR-4 of Section 8.2).
+ * EC-CSR-4 of Section 8.2); 16-bit absolute columns can be asked for instead, for the ablation of Section 8.3.
  * ecspmv_build_* runs the offline phase on the host (Sections 4, 5, 6); ecspmv_run is the
  * online phase (Section 7): one HIP kernel launch on a caller-supplied stream.
  *
@@ -33,7 +33,8 @@ extern "C" {
 
 #define ECSPMV_OK                 0
 #define ECSPMV_ERR_INVALID       -1  /* NULL pointer, bad size, ld < n, unsorted / duplicate / out-of-range CSR column */
-#define ECSPMV_ERR_UNSUPPORTED   -2  /* n > 65535, delta_bits not 4 or 8, max_granularity not in {1,2,4,8,16}, too many rows */
+#define ECSPMV_ERR_UNSUPPORTED   -2  /* n > 65535, delta_bits not 4, 8 or 16, max_granularity not in {1,2,4,8,16}, too many rows,
+                                        an option or call that does not exist for this kind of image */
 #define ECSPMV_ERR_NOMEM         -3  /* host allocation failed */
 #define ECSPMV_ERR_HIP           -4  /* a HIP call failed; ecspmv_last_hip_error() has its code */
 #define ECSPMV_ERR_NOT_UPLOADED  -5  /* ecspmv_run before ecspmv_upload */
@@ -43,12 +44,20 @@ typedef struct ecspmv_matrix ecspmv_matrix;     /* opaque: the host-side EC-CSR 
 typedef struct ecspmv_csr ecspmv_csr;           /* opaque: plain CSR (comparison kernel) */
 
 /* Options of the offline phase.  NULL, or a zeroed struct with struct_size set, gives the
- * defaults.  Fields beyond struct_size are taken as 0 (= default). */
+ * defaults.  Fields beyond struct_size are taken as 0 (= default).
+ * The paper leaves the clipping threshold of Section 5, the smallest useful block and the number of levels open.
+ * Here they are not options: blocks are clipped into fixed units of 64 columns and residual rows into units of 16
+ * entries (what a quarter of a wavefront, resp. a lane, handles per step), a block is useful from one unit on, and
+ * the number of levels follows from max_granularity.  What can be chosen instead is how the launch is cut
+ * (num_panels, threads_per_wg). */
 typedef struct ecspmv_build_opts {
     uint32_t struct_size;     /* sizeof(ecspmv_build_opts) as the caller compiled it */
     int32_t  delta_bits;      /* width of a delta index (Section 6.2, range R_P = 2^bits): 8 (EC-CSR-8) or 4
                                  (EC-CSR-4, Section 8.2: zero fillers every 15 columns, blocks only where 64 shared
-                                 columns follow one another within 15); 0 = 8 */
+                                 columns follow one another within 15); 0 = 8.  16 = index compression off: every
+                                 index is the 16-bit column itself, no fillers, no range limit on blocks (the first
+                                 step of the ablation of Section 8.3, through the same kernel; FP16 values and one
+                                 right-hand side only) */
     int32_t  max_granularity; /* largest block granularity g (rows per block, Section 4); 0 = 8 (4 for FP32 values);
                                  1 = no extraction */
     int32_t  max_rounds;      /* cap on extraction rounds per level (Algorithm 1, inner loop); 0 = 64 */
@@ -102,12 +111,14 @@ typedef struct ecspmv_stats_t {
 
 /* ---- offline phase (host) -------------------------------------------------------------------------- */
 
-/* Build from a dense row-major FP16 matrix.  W: host, m rows of n entries, row stride ld >= n (elements).
+/* Sections 4 (hierarchical block extraction, Algorithms 1 and 2), 5 (clipping, ordering) and 6 (EC-CSR encoding).
+ * Build from a dense row-major FP16 matrix.  W: host, m rows of n entries, row stride ld >= n (elements).
  * Caller keeps W.  *out receives a new handle (free with ecspmv_destroy).  m, n >= 1; n <= 65535. */
 int ecspmv_build_dense(const uint16_t *W, int64_t m, int64_t n, int64_t ld,
                        const ecspmv_build_opts *opts, ecspmv_matrix **out);
 
-/* Build from CSR.  rowptr: host, m+1 entries, rowptr[0] = 0, non-decreasing; col: host, strictly increasing
+/* The same from CSR (the form pruned weights usually come in; the paper's Section 3 takes "the sparse matrix").
+ * rowptr: host, m+1 entries, rowptr[0] = 0, non-decreasing; col: host, strictly increasing
  * within a row, in [0, n); val: host FP16 bits (entries equal to +-0 are dropped). */
 int ecspmv_build_csr(const int64_t *rowptr, const int32_t *col, const uint16_t *val,
                      int64_t m, int64_t n, const ecspmv_build_opts *opts, ecspmv_matrix **out);
@@ -122,10 +133,13 @@ int ecspmv_build_csr_f32(const int64_t *rowptr, const int32_t *col, const float 
 
 void ecspmv_destroy(ecspmv_matrix *A);          /* NULL is a no-op */
 
-/* Fill *st (st->struct_size must be set by the caller). */
+/* The figures of the paper's storage study (Section 8.2: bytes against CSR-32 / CSR-16; Table 2: padding) and of its
+ * objective (Section 4: x-access cost) for this image.  Fill *st (st->struct_size must be set by the caller). */
 int ecspmv_stats(const ecspmv_matrix *A, ecspmv_stats_t *st);
 
-/* Decode the image back to coordinate triples by walking it the way the kernel does, dropping padding.
+/* Decode the image back to coordinate triples by walking it the way the kernel does (columns by the recurrence of
+ * Section 6.2, I_k = I_0 + sum of deltas; values through the inverse of the permutation of Section 6.3.2), dropping
+ * padding.
  * Call with rows = cols = vals = NULL to get *nnz; then with host arrays of *nnz entries each (capacity
  * passed in *nnz).  Output order is image order (not sorted). */
 int ecspmv_decode(const ecspmv_matrix *A, int64_t *nnz, int32_t *rows, int32_t *cols, uint16_t *vals);
@@ -140,27 +154,45 @@ int ecspmv_block_sets(const ecspmv_matrix *A, int64_t *n_units, int64_t *n_rows,
 
 /* ---- device image ---------------------------------------------------------------------------------- */
 
-/* Size of the device image in bytes (a multiple of 256). */
+/* Library plumbing, no passage of the paper: size of the device image in bytes (a multiple of 256). */
 int ecspmv_device_bytes(const ecspmv_matrix *A, size_t *bytes);
 
-/* Copy the image into host memory (host_dst: host, >= ecspmv_device_bytes): for inspection, tests and caching.
- * The layout is the one paper_2507_12205_amd/csrc/ecspmv_format.h describes. */
+/* Library plumbing, no passage of the paper: copy the image into host memory (host_dst: host, >=
+ * ecspmv_device_bytes): for inspection, tests and caching.  Layout of the bytes (version 3; all little-endian):
+ *   [image header, 256 B: magic "ECSR", version, m, n, num_panels, threads_per_wg, panel_stride, meta_stride,
+ *    max_slots, lds_bytes (uint32 each), image_bytes, nnz (uint64), delta_bits, value_bits (uint32)]
+ *   [panel 0] ... [panel P-1], panel_stride bytes apart, then 4 KB of zeros.
+ *   panel = [header, 32 uint32: first row, rows, block slots, residual lane units, residual row segments, byte
+ *            offsets of the tables and arrays that follow, units per granularity]
+ *           [tables: first slot of each row (uint16), first residual lane unit of each row (uint32), output row of
+ *            each row (uint32: the paper's row_indices), per block unit its base column and the slots of its rows
+ *            (uint16), per residual chunk a 64-bit mask of lanes that start a row segment, per row segment its
+ *            base column]
+ *           [residual chunks: 64 lane units of 16 entries each: their indices, then their values, 128 bits per lane
+ *            and load]
+ *           [per granularity 16, 8, 4, 2: the units' indices (64 per unit), then their values (g per column,
+ *            permuted so that a 16-lane group loads 128 bits per lane)].
+ * The authoritative description, with every offset, is the format header that ships with the library's sources. */
 int ecspmv_export_image(const ecspmv_matrix *A, void *host_dst, size_t bytes);
 
-/* Copy the image into d_buf (device, 256-byte aligned, >= ecspmv_device_bytes, allocated and owned by the
+/* Library plumbing, no passage of the paper (the paper's format generation is "once at deployment", Section 8.1).
+ * Copy the image into d_buf (device, 256-byte aligned, >= ecspmv_device_bytes, allocated and owned by the
  * caller) on `stream`, and remember d_buf in the handle.  Returns after the copy has completed. */
 int ecspmv_upload(ecspmv_matrix *A, void *d_buf, size_t bytes, void *stream);
 
 /* ---- online phase ---------------------------------------------------------------------------------- */
 
-/* y = W x (overwrites y; every one of the m entries is written).  d_x: device, n FP16, 2-byte aligned
+/* The online phase (Section 7; the product is the one of Sections 1 and 2.2: Y = W X with a single column).
+ * y = W x (overwrites y; every one of the m entries is written).  d_x: device, n FP16, 2-byte aligned
  * (16-byte alignment takes the faster staging path).  d_y: device, m FP16.  x and y must not overlap.
  * For a matrix built with ecspmv_build_*_f32, x and y are FP32 (4-byte aligned).
- * Asynchronous on `stream`: exactly one kernel launch, no allocation, no memset, no host synchronisation.
+ * Asynchronous on `stream`: exactly one kernel launch, no allocation (host or device), no memset, no host
+ * synchronisation, nothing that can throw.
  * x must be finite: padding zeros are multiplied with x entries. */
 int ecspmv_run(const ecspmv_matrix *A, const void *d_x, void *d_y, void *stream);
 
-/* The same for `count` independent SpMVs in one kernel launch per 16 matrices (a launch also ends where the
+/* No passage of the paper (its kernel is launched once per matrix): the same for `count` independent SpMVs in one
+ * kernel launch per 16 matrices (a launch also ends where the
  * delta width or the value width changes from one matrix to the next): y_i = W_i x_i.  As, d_xs, d_ys:
  * host arrays of `count` handles / device pointers.  The SpMVs must not depend on one another (no y_i may be an
  * x_j of the same call).  Meant for the projections of a decoder layer that do not depend on one another:
@@ -182,6 +214,8 @@ int ecspmv_run_batch(const ecspmv_matrix *const *As, const void *const *d_xs, vo
 int ecspmv_run_multi(const ecspmv_matrix *A, const void *d_X, void *d_Y, int32_t nb, void *stream);
 
 /* ---- comparison: plain CSR (int32 column index + FP16 value per entry, one wavefront per row) ------- */
+/* The CSR-32 format the paper's Section 8.2 measures storage against, with a kernel of its own (not one of the
+ * paper's comparison libraries). */
 
 int ecspmv_csr_build_dense(const uint16_t *W, int64_t m, int64_t n, int64_t ld, ecspmv_csr **out);
 void ecspmv_csr_destroy(ecspmv_csr *C);
@@ -195,6 +229,19 @@ int ecspmv_csr_run(const ecspmv_csr *C, const void *d_x, void *d_y, void *stream
  * workgroups of 1024 threads and writes one 32-bit checksum per workgroup to d_out (device, num_wg words).
  * One launch, asynchronous on `stream`. */
 int ecspmv_stream_read(const void *d_buf, size_t bytes, void *d_out, int32_t num_wg, void *stream);
+
+/* The same bytes read the way a launch of the SpMV kernel reads an image: workgroup w of `num_wg` workgroups of
+ * `threads_per_wg` (256, 512 or 1024) threads reads the w-th contiguous slice of the buffer, two 128-bit loads in
+ * flight per lane.  The fastest plain read found for 20-50 MB in a launch of its own: the time of this launch is the
+ * floor under a lone SpMV launch that reads as many bytes.  d_out: device, num_wg words.  One launch, asynchronous. */
+int ecspmv_stream_read_sliced(const void *d_buf, size_t bytes, void *d_out, int32_t num_wg, int32_t threads_per_wg,
+                              void *stream);
+
+/* `count` launches, one after the other on `stream`, of `num_wg` workgroups of `threads_per_wg` (a multiple of 64,
+ * <= 1024) threads that read nothing and store one word per workgroup to d_out (device, num_wg words): what a launch
+ * costs by itself when launches follow one another on a stream (submitted from one host loop, so that the host is
+ * not what is timed).  Asynchronous. */
+int ecspmv_empty_launch(void *d_out, int32_t num_wg, int32_t threads_per_wg, int32_t count, void *stream);
 
 /* ---- errors ---------------------------------------------------------------------------------------- */
 

@@ -7,5 +7,6 @@ from . import binding  # noqa: F401
 from .binding import (  # noqa: F401
     EcspmvError, Matrix, CsrMatrix, make_opts, ecspmv_build_dense, ecspmv_build_csr,
     ecspmv_build_dense_f32, ecspmv_build_csr_f32,
-    ecspmv_csr_build_dense, ecspmv_stream_read, ecspmv_run_batch, Batch,
+    ecspmv_csr_build_dense, ecspmv_stream_read, ecspmv_stream_read_sliced, ecspmv_empty_launch,
+    ecspmv_run_batch, Batch,
 )

@@ -26,7 +26,7 @@ EXPORTS = (
     "ecspmv_stats", "ecspmv_decode", "ecspmv_decode_f32",
     "ecspmv_block_sets", "ecspmv_device_bytes", "ecspmv_export_image", "ecspmv_upload", "ecspmv_run", "ecspmv_run_batch", "ecspmv_run_multi",
     "ecspmv_csr_build_dense", "ecspmv_csr_destroy", "ecspmv_csr_device_bytes", "ecspmv_csr_upload",
-    "ecspmv_csr_run", "ecspmv_stream_read", "ecspmv_strerror", "ecspmv_last_hip_error",
+    "ecspmv_csr_run", "ecspmv_stream_read", "ecspmv_stream_read_sliced", "ecspmv_empty_launch", "ecspmv_strerror", "ecspmv_last_hip_error",
 )
 
 
@@ -104,6 +104,8 @@ def lib() -> ctypes.CDLL:
     L.ecspmv_csr_upload.argtypes = [c_void_p, c_void_p, c_size_t, c_void_p]
     L.ecspmv_csr_run.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p]
     L.ecspmv_stream_read.argtypes = [c_void_p, c_size_t, c_void_p, c_int32, c_void_p]
+    L.ecspmv_stream_read_sliced.argtypes = [c_void_p, c_size_t, c_void_p, c_int32, c_int32, c_void_p]
+    L.ecspmv_empty_launch.argtypes = [c_void_p, c_int32, c_int32, c_int32, c_void_p]
     L.ecspmv_strerror.argtypes = [c_int]
     L.ecspmv_strerror.restype = c_char_p
     L.ecspmv_last_hip_error.argtypes = []
@@ -321,3 +323,14 @@ def ecspmv_csr_build_dense(W: np.ndarray) -> CsrMatrix:
 def ecspmv_stream_read(d_buf: int, nbytes: int, d_out: int, num_wg: int, stream: int = 0) -> None:
     _check(lib().ecspmv_stream_read(c_void_p(d_buf), nbytes, c_void_p(d_out), num_wg, c_void_p(stream)),
            "ecspmv_stream_read")
+
+
+def ecspmv_stream_read_sliced(d_buf: int, nbytes: int, d_out: int, num_wg: int, threads_per_wg: int,
+                              stream: int = 0) -> None:
+    _check(lib().ecspmv_stream_read_sliced(c_void_p(d_buf), nbytes, c_void_p(d_out), num_wg, threads_per_wg,
+                                           c_void_p(stream)), "ecspmv_stream_read_sliced")
+
+
+def ecspmv_empty_launch(d_out: int, num_wg: int, threads_per_wg: int, count: int = 1, stream: int = 0) -> None:
+    _check(lib().ecspmv_empty_launch(c_void_p(d_out), num_wg, threads_per_wg, count, c_void_p(stream)),
+           "ecspmv_empty_launch")

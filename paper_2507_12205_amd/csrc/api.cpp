@@ -461,7 +461,28 @@ int ecspmv_stream_read(const void *d_buf, size_t bytes, void *d_out, int32_t num
 {
     if (!d_buf || !d_out || num_wg <= 0 || (bytes & 15) || (reinterpret_cast<uintptr_t>(d_buf) & 15))
         return ECSPMV_ERR_INVALID;
-    return hip_status(ecs::launch_stream_read(d_buf, bytes, d_out, (uint32_t)num_wg, stream));
+    return hip_status(ecs::launch_stream_read(d_buf, bytes, d_out, (uint32_t)num_wg, 1024u, false, stream));
+}
+
+int ecspmv_stream_read_sliced(const void *d_buf, size_t bytes, void *d_out, int32_t num_wg, int32_t threads_per_wg,
+                              void *stream)
+{
+    if (!d_buf || !d_out || num_wg <= 0 || (bytes & 15) || (reinterpret_cast<uintptr_t>(d_buf) & 15))
+        return ECSPMV_ERR_INVALID;
+    if (threads_per_wg != 256 && threads_per_wg != 512 && threads_per_wg != 1024) return ECSPMV_ERR_INVALID;
+    return hip_status(ecs::launch_stream_read(d_buf, bytes, d_out, (uint32_t)num_wg, (uint32_t)threads_per_wg, true,
+                                              stream));
+}
+
+int ecspmv_empty_launch(void *d_out, int32_t num_wg, int32_t threads_per_wg, int32_t count, void *stream)
+{
+    if (!d_out || num_wg <= 0 || count <= 0 || threads_per_wg < 64 || threads_per_wg > 1024 || (threads_per_wg & 63))
+        return ECSPMV_ERR_INVALID;
+    for (int32_t i = 0; i < count; ++i) {
+        int s = hip_status(ecs::launch_empty(d_out, (uint32_t)num_wg, (uint32_t)threads_per_wg, stream));
+        if (s) return s;
+    }
+    return ECSPMV_OK;
 }
 
 #ifdef ECS_TRACE

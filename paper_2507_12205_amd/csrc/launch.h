@@ -32,7 +32,9 @@ int launch_ecspmv_multi(const EcsBatch &batch, uint32_t threads, uint32_t lds_by
                         uint32_t delta_bits, uint32_t value_bits, uint32_t nb, void *stream);
 int launch_csr(const void *d_rowptr, const void *d_col, const void *d_val, const void *d_x, void *d_y, uint32_t m,
                void *stream);
-int launch_stream_read(const void *d_buf, uint64_t bytes, void *d_out, uint32_t num_wg, void *stream);
+int launch_stream_read(const void *d_buf, uint64_t bytes, void *d_out, uint32_t num_wg, uint32_t threads, bool sliced,
+                       void *stream);
+int launch_empty(void *d_out, uint32_t num_wg, uint32_t threads, void *stream);
 int copy_to_device(void *d_dst, const void *h_src, uint64_t bytes, void *stream);
 int device_lds_limit(int *bytes);
 int current_device(int *dev);

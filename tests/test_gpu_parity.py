@@ -209,6 +209,26 @@ def test_stream_read_checksum(E):
     assert got == want
 
 
+@pytest.mark.parametrize("nwords,nwg,threads", [(1 << 20, 256, 1024), ((1 << 20) + 4 * 37, 100, 512), (4 * 50, 7, 256)])
+def test_sliced_read_checksum_and_empty_launch(E, nwords, nwg, threads):
+    """The launch-floor aids: the sliced read covers every 16 bytes exactly once (ragged slices and workgroups with
+    nothing to read included); the empty launch stores one word per workgroup."""
+    import torch
+    buf = torch.randint(0, 2 ** 31 - 1, (nwords,), dtype=torch.int32, device="cuda")
+    out = torch.full((nwg,), 5, dtype=torch.int32, device="cuda")
+    sh = torch.cuda.current_stream().cuda_stream
+    E.ecspmv_stream_read_sliced(buf.data_ptr(), nwords * 4, out.data_ptr(), nwg, threads, sh)
+    torch.cuda.synchronize()
+    got = np.bitwise_xor.reduce(out.cpu().numpy().view(np.uint32))
+    want = np.bitwise_xor.reduce(buf.cpu().numpy().view(np.uint32))
+    assert got == want
+    E.ecspmv_empty_launch(out.data_ptr(), nwg, threads, 3, sh)
+    torch.cuda.synchronize()
+    assert np.array_equal(out.cpu().numpy(), np.arange(nwg, dtype=np.int32))
+    with pytest.raises(E.EcspmvError):
+        E.ecspmv_stream_read_sliced(buf.data_ptr(), nwords * 4, out.data_ptr(), nwg, 384, sh)
+
+
 def test_errors_from_the_abi(E):
     import torch
     W, x = gen.small_random(20, 100, 0.5, 1)
