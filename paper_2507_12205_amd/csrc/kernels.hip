@@ -588,15 +588,6 @@ __global__ __launch_bounds__(1024) void ecspmv_kernel(const uint32_t count, cons
     c.tr.sel = c.trace ? (uint32_t)(trace_words >> 56) : 0xFFFFFFFFu;      // the point to stamp rides in the top byte
 #endif
 
-    // Everything the workgroup needs first is requested at once: the panel header (wave-uniform: scalar loads), and
-    // the panel's tables and x on their way to LDS, as one list of 16-byte pieces [tables | x] with K pieces per
-    // thread.  These loads are unconditional (indices wrapped), so none of them makes a later wait inexact; K is a
-    // template parameter, the smallest that covers the list, because every wave-wide load costs issue time on the
-    // way to the first barrier whether its lanes are needed or not.
-    // The header travels through the vector memory path: lanes 0..7 of every wavefront load 16 bytes each (the other
-    // lanes repeat them) and the words are then read out of the lanes into scalar registers.  Scalar loads of the same
-    // 128 bytes by all wavefronts of a workgroup are served one wavefront after the other (measured: the last of 16
-    // wavefronts has its header 1.4 us after the workgroup started, against 0.5 us this way).
     // Everything the workgroup needs first is requested at once: the panel header, and the panel's tables and x on
     // their way to LDS, as one list of 16-byte pieces [tables | x] with K pieces per thread.  These loads are
     // unconditional (indices clamped or folded), so none of them makes a later wait inexact; K is a template parameter,
