@@ -478,6 +478,30 @@ def main():
             reads[f"{m}x{n}"] = {"bytes": nbytes, "read_us": round(best[0], 3), "workgroups": best[1], "threads": best[2],
                                  "spmv_us": spmv_us, "spmv_over_read": round(spmv_us / best[0], 3) if spmv_us else None}
             step_floor += best[0] * sum(1 for e in mats[0] if (e["m"], e["n"]) == (m, n))
+        # the same for the launches of mode `groups` (the bytes of the SpMVs that share a launch, read in one launch)
+        gsum, glist = 0.0, []
+        for g in group_of([e["name"] for e in mats[0]]):
+            nbytes = int(sum(mats[0][i]["bytes"] for i in g)) // 256 * 256
+            nbuf = max(2, pool.numel() // nbytes)
+            best = None
+            for nwg, thr in ((256, 1024), (512, 512), (1024, 512), (1024, 256), (2048, 256)):
+                for r in range(nbuf):
+                    E.ecspmv_stream_read_sliced(pool.data_ptr() + r * nbytes, nbytes, nul.data_ptr(), nwg, thr, sh)
+                torch.cuda.synchronize()
+                ev0.record(stream)
+                reps = 3 * nbuf
+                for r in range(reps):
+                    E.ecspmv_stream_read_sliced(pool.data_ptr() + (r % nbuf) * nbytes, nbytes, nul.data_ptr(), nwg, thr, sh)
+                ev1.record(stream)
+                torch.cuda.synchronize()
+                us = ev0.elapsed_time(ev1) * 1e3 / reps
+                if best is None or us < best:
+                    best = us
+            glist.append({"spmvs": "+".join(mats[0][i]["name"] for i in g), "bytes": nbytes, "read_us": round(best, 3)})
+            gsum += best
+        floor["plain_read_group_launches_cold"] = glist
+        floor["step_of_group_launches_us"] = round(gsum, 3)
+        floor["step_of_group_launches_pct_of_hbm_peak"] = round(100.0 * layer_bytes[0] / (gsum * 1e-6) / 1e9 / HBM_PEAK_GBPS, 2)
         del pool
         floor["plain_read_lone_launch_cold"] = reads
         floor["step_of_lone_launches_us"] = round(step_floor, 3)

@@ -716,7 +716,9 @@ __global__ __launch_bounds__(1024) void ecspmv_kernel(const uint32_t count, cons
 
     // every row: add its slots and the partial sums of its lane units in a fixed order (16 lanes stride over them,
     // then a fixed tree), store FP16.  (Measured and not kept: a whole wavefront per row for long rows, 64 lanes
-    // striding: 2 % slower on the decoder-layer shapes; four LDS reads issued ahead of the additions: no difference.)
+    // striding: 2 % slower on the decoder-layer shapes; four unconditional LDS reads issued ahead of the
+    // additions, checked in the generated code: no difference, the final pass of one workgroup overlaps the chunks of
+    // others.)
     const uint32_t nrows = hdr[PH_NROWS];
     const uint32_t *rowidx = reinterpret_cast<const uint32_t *>(meta + hdr[PH_ROWIDX_OFF]);   // the output row of each row
     const uint16_t *rowslot = reinterpret_cast<const uint16_t *>(meta + hdr[PH_ROWSLOT_OFF]);
