@@ -117,7 +117,7 @@ typedef struct ecspmv_stats_t {
 int ecspmv_build_dense(const uint16_t *W, int64_t m, int64_t n, int64_t ld,
                        const ecspmv_build_opts *opts, ecspmv_matrix **out);
 
-/* The same from CSR (the form pruned weights usually come in; the paper's Section 3 takes "the sparse matrix").
+/* The same from CSR (the form pruned weights usually come in).
  * rowptr: host, m+1 entries, rowptr[0] = 0, non-decreasing; col: host, strictly increasing
  * within a row, in [0, n); val: host FP16 bits (entries equal to +-0 are dropped). */
 int ecspmv_build_csr(const int64_t *rowptr, const int32_t *col, const uint16_t *val,
