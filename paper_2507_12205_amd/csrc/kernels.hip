@@ -397,6 +397,47 @@ template <int DB, bool FENCE, int NB, int VW>
 __device__ __forceinline__ void compute_chunk(const Ctx &c, const EcsRChunk *rch, const EcsREntry *ren, float *part,
                                               uint32_t ch, const ChunkRegs<DB, VW> &r)
 {
+    if constexpr (DB == 4 && NB == 1 && VW == 2) {
+        // 4-bit deltas, FP16, one right-hand side: the 16 prefix sums of a lane are made eight at a time inside 32-bit
+        // words, already doubled (they are byte offsets into the FP16 copy of x in LDS).  With lo / hi the even / odd
+        // nibbles of a word spread to bytes (times two), T = bytewise running sum of lo + hi: byte k of T is the
+        // prefix up to nibble 2k + 1, byte k of T - hi the prefix up to nibble 2k.  Eight deltas of at most 15 add
+        // up to 120, doubled 240: a byte holds it.  Each gather address is then one add of a byte of such a word.
+        constexpr uint32_t M2 = 0x1E1E1E1Eu;
+        uint32_t pe[2], po[2];
+#pragma unroll
+        for (int w = 0; w < 2; ++w) {
+            const uint32_t lo = (r.d[w] << 1) & M2, hi = (r.d[w] >> 3) & M2;
+            uint32_t t = lo + hi;
+            // t += t << 8; t += t << 16: written as two shift-adds (the compiler would make a 32-bit multiply by
+            // 0x01010101 of it, which runs at a quarter of the rate)
+            asm("v_lshl_add_u32 %0, %1, 8, %1" : "=v"(t) : "v"(t));
+            asm("v_lshl_add_u32 %0, %1, 16, %1" : "=v"(t) : "v"(t));
+            po[w] = t, pe[w] = t - hi;
+        }
+        const uint32_t tot0 = po[0] >> 24;                                 // twice the sum of the first eight deltas
+        const int run = (int)((tot0 + (po[1] >> 24)) >> 1);
+        const int incl = wave64_incl_scan(run);
+        const uint64_t mask = rch[ch].head_mask;
+        const uint64_t le = (c.lane == 63) ? ~0ull : ((2ull << c.lane) - 1ull);
+        const int seg = __popcll(mask & le) - 1;
+        const int start = ren[rch[ch].entry0 + seg].c + incl - run;
+        const uint32_t base[2] = {2u * (uint32_t)start, 2u * (uint32_t)start + tot0};
+        const uint8_t *xb = reinterpret_cast<const uint8_t *>(c.xs);
+        float acc = 0.0f;
+        const uint32_t vw[8] = {r.v[0].x, r.v[0].y, r.v[0].z, r.v[0].w, r.v[1].x, r.v[1].y, r.v[1].z, r.v[1].w};
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const uint32_t src = (i & 1) ? po[i >> 3] : pe[i >> 3];
+            const uint32_t off = base[i >> 3] + ((src >> (8 * ((i & 7) >> 1))) & 0xFFu);
+            const float xv = half_bits_to_float(*reinterpret_cast<const uint16_t *>(xb + off));
+            const uint32_t word = vw[i >> 1];
+            acc = fma_h((i & 1) ? (word >> 16) : (word & 0xFFFF), xv, acc);
+        }
+        part[64u * ch + c.lane] = acc;
+        if constexpr (FENCE) __builtin_amdgcn_sched_barrier(0);
+        return;
+    }
     uint32_t rel[16];
     int start = 0;
     if constexpr (DB == 16) {                       // the indices are the columns: no prefix, no scan, no segment base
