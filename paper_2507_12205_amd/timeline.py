@@ -162,11 +162,10 @@ def main():
                          last_us=round(float(np.mean([at[r][ok[r]].max() for r in use])), 3),
                          last_wave_of_wg_median_us=round(float(np.mean(wg_last)), 3),
                          wavefronts=int(ok[use].sum() // len(use))))
-        if True:
-            span = float(np.mean([np.where(valid[r], end[r], -np.inf).max() for r in use]))
-            # from the last instruction of a launch to the first of the next, on the constant-rate clock
-            last_real = np.where(valid, T[..., 4], 0).max(axis=(1, 2))
-            gap = float(np.mean((real0[1:] - last_real[:-1])[1:]) * 0.01)
+        span = float(np.mean([np.where(valid[r], end[r], -np.inf).max() for r in use]))
+        # from the last instruction of a launch to the first of the next, on the constant-rate clock
+        last_real = np.where(valid, T[..., 4], 0).max(axis=(1, 2))
+        gap = float(np.mean((real0[1:] - last_real[:-1])[1:]) * 0.01)
     if args.raw:
         np.savez_compressed(args.raw, **{f"stamp{k}": v for k, v in raw.items()})
     out = dict(workload=f"config {cfg.cid} {name} {m}x{n}, EC-CSR-{args.delta_bits}, {copies} cold copies, "
