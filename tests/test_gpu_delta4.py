@@ -159,3 +159,34 @@ def test_mixed_widths_in_one_batch_call(E):
     torch.cuda.synchronize()
     for i, (y, l) in enumerate(zip(ys, lone)):
         assert np.array_equal(y.cpu().numpy().view(np.uint16), l.view(np.uint16)), i
+
+
+def test_deltas_at_both_ends_of_their_range(E):
+    """Gap patterns that drive the lane-local prefix sums of the 4-bit path to their limits: every gap 15 (eight of them
+    add up to 120, the most a byte-wide doubled prefix has to hold), every gap 1, 15 and 1 in turn, eight times 15 then
+    eight times 1 and the reverse (one word of a lane full, the other nearly empty), and a gap of 14.  Rows are long enough
+    for several chunks; x = e_j must return column j bit for bit for columns near the start, the middle and the end of a
+    row, where every earlier prefix and every lane total of the chunk has gone into the address."""
+    import torch
+    n = 60000
+    pats = [[15], [1], [15, 1], [15] * 8 + [1] * 8, [1] * 8 + [15] * 8, [14], [15] * 3 + [2]]
+    W = np.zeros((len(pats), n), dtype=np.float16)
+    rng = np.random.default_rng(5)
+    for i, p in enumerate(pats):
+        cols = np.cumsum(np.resize(np.array(p), 6000)) - p[0]
+        cols = cols[cols < n]
+        W[i, cols] = (rng.standard_normal(cols.size) * 0.02).astype(np.float16)
+        W[i, cols[W[i, cols] == 0]] = np.float16(0.01)
+    x = rng.standard_normal(n).astype(np.float16)
+    for panels in (1, 3):
+        A, _ = check(E, W, x, f"gap patterns, {panels} panels", max_granularity=1, num_panels=panels)
+        st = A.ecspmv_stats()
+        assert st.gap_pad_elements == 0 and st.delta_bits == 4
+        for j in (0, 15, 16, 30, 1785, 1800, 29985, 30000, 59985, int(np.nonzero(W[1])[0][-1])):
+            e = np.zeros(n, dtype=np.float16)
+            e[j] = 1.0
+            xd = torch.from_numpy(e.view(np.int16)).cuda().view(torch.float16)
+            yd = torch.full((len(pats),), float("nan"), dtype=torch.float16, device="cuda")
+            E.device.run(A, xd, yd)
+            torch.cuda.synchronize()
+            assert np.array_equal(yd.cpu().numpy().view(np.uint16) & 0x7FFF, W[:, j].view(np.uint16) & 0x7FFF), j
