@@ -39,6 +39,8 @@ extern "C" {
 #define ECSPMV_ERR_HIP           -4  /* a HIP call failed; ecspmv_last_hip_error() has its code */
 #define ECSPMV_ERR_NOT_UPLOADED  -5  /* ecspmv_run before ecspmv_upload */
 #define ECSPMV_ERR_TOO_SMALL     -6  /* caller's buffer is smaller than required */
+#define ECSPMV_ERR_INTERNAL      -7  /* anything else that went wrong inside a host-side call (e.g. a worker thread could
+                                        not be started); the handle or output is not produced */
 
 typedef struct ecspmv_matrix ecspmv_matrix;     /* opaque: the host-side EC-CSR image of one matrix */
 typedef struct ecspmv_csr ecspmv_csr;           /* opaque: plain CSR (comparison kernel) */

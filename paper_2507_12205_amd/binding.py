@@ -15,7 +15,7 @@ import numpy as np
 from . import build as _build
 
 OK = 0
-ERR_INVALID, ERR_UNSUPPORTED, ERR_NOMEM, ERR_HIP, ERR_NOT_UPLOADED, ERR_TOO_SMALL = -1, -2, -3, -4, -5, -6
+ERR_INVALID, ERR_UNSUPPORTED, ERR_NOMEM, ERR_HIP, ERR_NOT_UPLOADED, ERR_TOO_SMALL, ERR_INTERNAL = -1, -2, -3, -4, -5, -6, -7
 FLAG_GLOBAL_MATCHING = 1
 FLAG_NO_REORDER = 2
 FLAG_KEEP_SMALL_SETS = 4

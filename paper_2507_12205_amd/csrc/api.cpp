@@ -135,6 +135,8 @@ int decode_t(const ecspmv_matrix *A, int value_bits, int64_t *nnz, int32_t *rows
         return ECSPMV_OK;
     } catch (const std::bad_alloc &) {
         return ECSPMV_ERR_NOMEM;
+    } catch (...) {                                  // nothing may leave through the C ABI (a worker thread that could
+        return ECSPMV_ERR_INTERNAL;                  // not be started, for instance)
     }
 }
 
@@ -156,6 +158,8 @@ int ecspmv_build_dense(const uint16_t *W, int64_t m, int64_t n, int64_t ld, cons
         return finish_build(A, bp, out);
     } catch (const std::bad_alloc &) {
         return ECSPMV_ERR_NOMEM;
+    } catch (...) {                                  // nothing may leave through the C ABI (a worker thread that could
+        return ECSPMV_ERR_INTERNAL;                  // not be started, for instance)
     }
 }
 
@@ -174,6 +178,8 @@ int ecspmv_build_csr(const int64_t *rowptr, const int32_t *col, const uint16_t *
         return finish_build(A, bp, out);
     } catch (const std::bad_alloc &) {
         return ECSPMV_ERR_NOMEM;
+    } catch (...) {                                  // nothing may leave through the C ABI (a worker thread that could
+        return ECSPMV_ERR_INTERNAL;                  // not be started, for instance)
     }
 }
 
@@ -191,6 +197,8 @@ int ecspmv_build_dense_f32(const float *W, int64_t m, int64_t n, int64_t ld, con
         return finish_build(A, bp, out);
     } catch (const std::bad_alloc &) {
         return ECSPMV_ERR_NOMEM;
+    } catch (...) {                                  // nothing may leave through the C ABI (a worker thread that could
+        return ECSPMV_ERR_INTERNAL;                  // not be started, for instance)
     }
 }
 
@@ -209,6 +217,8 @@ int ecspmv_build_csr_f32(const int64_t *rowptr, const int32_t *col, const float 
         return finish_build(A, bp, out);
     } catch (const std::bad_alloc &) {
         return ECSPMV_ERR_NOMEM;
+    } catch (...) {                                  // nothing may leave through the C ABI (a worker thread that could
+        return ECSPMV_ERR_INTERNAL;                  // not be started, for instance)
     }
 }
 
@@ -259,6 +269,8 @@ int ecspmv_block_sets(const ecspmv_matrix *A, int64_t *n_units, int64_t *n_rows,
         return ECSPMV_OK;
     } catch (const std::bad_alloc &) {
         return ECSPMV_ERR_NOMEM;
+    } catch (...) {                                  // nothing may leave through the C ABI (a worker thread that could
+        return ECSPMV_ERR_INTERNAL;                  // not be started, for instance)
     }
 }
 
@@ -424,6 +436,8 @@ int ecspmv_csr_build_dense(const uint16_t *W, int64_t m, int64_t n, int64_t ld, 
         return ECSPMV_OK;
     } catch (const std::bad_alloc &) {
         return ECSPMV_ERR_NOMEM;
+    } catch (...) {                                  // nothing may leave through the C ABI (a worker thread that could
+        return ECSPMV_ERR_INTERNAL;                  // not be started, for instance)
     }
 }
 
@@ -506,6 +520,7 @@ const char *ecspmv_strerror(int status)
     case ECSPMV_ERR_HIP: return "HIP call failed (see ecspmv_last_hip_error)";
     case ECSPMV_ERR_NOT_UPLOADED: return "matrix has no device image yet";
     case ECSPMV_ERR_TOO_SMALL: return "buffer too small";
+    case ECSPMV_ERR_INTERNAL: return "unexpected failure inside the library";
     default: return "unknown status";
     }
 }

@@ -7,6 +7,9 @@
 #include <atomic>
 #include <chrono>
 #include <cstring>
+#include <exception>
+#include <mutex>
+#include <system_error>
 #include <thread>
 
 namespace ecs {
@@ -24,18 +27,38 @@ static void parallel_for(int64_t count, int threads, F &&body)
         for (int64_t i = 0; i < count; ++i) body(i);
         return;
     }
+    // An exception in a worker (out of memory) must not end the process: the first one is kept, the other workers
+    // stop taking items, and it is thrown again in the caller once every worker has been joined.  If a worker cannot
+    // be started the ones already running do all the work.
     std::atomic<int64_t> next(0);
-    std::vector<std::thread> pool;
-    pool.reserve(threads);
-    for (int t = 0; t < threads; ++t)
-        pool.emplace_back([&]() {
+    std::atomic<bool> failed(false);
+    std::exception_ptr first;
+    std::mutex first_lock;
+    auto work = [&]() {
+        try {
             for (;;) {
-                int64_t i = next.fetch_add(1);
-                if (i >= count) break;
+                const int64_t i = next.fetch_add(1);
+                if (i >= count || failed.load(std::memory_order_relaxed)) break;
                 body(i);
             }
-        });
+        } catch (...) {
+            std::lock_guard<std::mutex> g(first_lock);
+            if (!first) first = std::current_exception();
+            failed.store(true);
+        }
+    };
+    std::vector<std::thread> pool;
+    pool.reserve(threads);
+    for (int t = 0; t + 1 < threads; ++t) {
+        try {
+            pool.emplace_back(work);
+        } catch (const std::system_error &) {
+            break;
+        }
+    }
+    work();                                           // the calling thread is the last worker
     for (auto &th : pool) th.join();
+    if (first) std::rethrow_exception(first);
 }
 
 static inline uint32_t align_up(uint32_t v, uint32_t a) { return (v + a - 1) / a * a; }

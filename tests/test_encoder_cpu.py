@@ -69,6 +69,9 @@ def test_error_paths_without_gpu():
     assert lib.ecspmv_run_batch(hs, odd, ptrs, 2, None) == B.ERR_INVALID
     lib.ecspmv_destroy(None)                                                                                 # no-op
     assert lib.ecspmv_strerror(B.ERR_TOO_SMALL).decode() == "buffer too small"
+    texts = {lib.ecspmv_strerror(c).decode() for c in (B.ERR_INVALID, B.ERR_UNSUPPORTED, B.ERR_NOMEM, B.ERR_HIP,
+                                                      B.ERR_NOT_UPLOADED, B.ERR_TOO_SMALL, B.ERR_INTERNAL)}
+    assert len(texts) == 7 and "unknown status" not in texts and lib.ecspmv_strerror(-99).decode() == "unknown status"
 
 
 def test_csr_input_matches_dense_input_and_is_validated():
