@@ -294,7 +294,8 @@ __device__ __forceinline__ void compute_unit(const Ctx &c, const uint16_t *utab,
 // A set's chunks c0, c0 + W, c0 + 2W, ... belong to this wavefront.  DEPTH register buffers take turns: all are
 // requested before anything is computed, and each is refilled right after it has been consumed, so a wavefront
 // always has its next DEPTH chunks on the way (the double buffering of Section 7, deeper and without copies).
-template <int G, int DB, int DEPTH, int NB, int VW>
+// STRAIGHT: the chunks requested in the prologue are computed in branch-free code (see run()).
+template <int G, int DB, int DEPTH, int NB, int VW, bool STRAIGHT = false>
 struct BlockSet {
     UnitRegs<G, VW> buf[DEPTH];
     uint32_t nu, n, c0, bd_off, bv_off;
@@ -321,13 +322,31 @@ struct BlockSet {
         // keeps the wait counts exact.
 #pragma unroll
         for (int d = 0; d < DEPTH; ++d) {
-            const bool have = (uint32_t)d < n;
+            // (STRAIGHT: a missing chunk re-reads the set's last unit, whose columns are real ones, because it will be
+            // computed and ignored; only a panel with no unit of this granularity at all falls back to the header)
+            const bool have = STRAIGHT ? nu > 0u : (uint32_t)d < n;
             load_unit<G, DB, VW>(c, have ? bd_off : 0u, have ? bv_off : 0u, have ? unit_of(c, d) : 0u, have ? nu : 1u, buf[d]);
         }
     }
     __device__ __forceinline__ void run(const Ctx &c)
     {
         uint32_t i = 0;
+        if constexpr (STRAIGHT) {
+            // The first DEPTH chunks in code without a branch that depends on how many chunks this wavefront has (a unit
+            // index past the end is computed on the last unit's data and stores nothing).  Loads of another set have
+            // been issued since the prologue (the residual set's, after the first barrier); where paths with different
+            // loads in flight meet, the compiler's wait for this set's data turns into a wait for those younger loads
+            // as well, and the first block chunk then waits for the residual chunk's whole round trip.
+            if (nu > 0u) {
+#pragma unroll
+                for (int d = 0; d < DEPTH; ++d) compute_unit<G, DB, NB, VW>(c, utab, unit_of(c, d), nu, buf[d]);
+            }
+            if (n <= (uint32_t)DEPTH) return;
+#pragma unroll
+            for (int d = 0; d < DEPTH; ++d)
+                if ((uint32_t)(DEPTH + d) < n) load_unit<G, DB, VW>(c, bd_off, bv_off, unit_of(c, DEPTH + d), nu, buf[d]);
+            i = DEPTH;
+        }
         for (; i + 2 * DEPTH - 1 < n; i += DEPTH) {    // chunks i + DEPTH ... i + 2 DEPTH - 1 exist: unconditional refills
 #pragma unroll
             for (int d = 0; d < DEPTH; ++d) {
@@ -645,7 +664,9 @@ __global__ __launch_bounds__(1024) void ecspmv_kernel(const uint32_t count, cons
     BlockSet<16, DB, 1, NB, VW> b16;
     BlockSet<8, DB, 1, NB, VW> b8;
     BlockSet<4, DB, wide ? 1 : D4, NB, VW> b4;
-    BlockSet<2, DB, wide ? 2 : D2, NB, VW> b2;
+    // (one block set in a launch of its own: its first chunks are computed while the residual set, requested after
+    // the first barrier, is still on its way)
+    BlockSet<2, DB, wide ? 2 : D2, NB, VW, TM == 1 && !BATCH && NB == 1 && VW == 2> b2;
     ResidualSet<DB, wide ? 2 : (TM == 0 && BATCH ? DR0B : DR), TM == 0 && BATCH, NB, VW> rs;
     // A lone launch of an image with one block set requests the residual set's first chunks only after the barrier:
     // a wavefront cannot pass the barrier before its requests are out, and with both sets requested up front the
