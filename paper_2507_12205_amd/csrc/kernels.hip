@@ -294,7 +294,7 @@ __device__ __forceinline__ void compute_unit(const Ctx &c, const uint16_t *utab,
 // A set's chunks c0, c0 + W, c0 + 2W, ... belong to this wavefront.  DEPTH register buffers take turns: all are
 // requested before anything is computed, and each is refilled right after it has been consumed, so a wavefront
 // always has its next DEPTH chunks on the way (the double buffering of Section 7, deeper and without copies).
-// STRAIGHT: the chunks requested in the prologue are computed in branch-free code (see run()).
+// STRAIGHT: the chunks requested in the prologue are computed by run_first(), before any set issues further loads.
 template <int G, int DB, int DEPTH, int NB, int VW, bool STRAIGHT = false>
 struct BlockSet {
     UnitRegs<G, VW> buf[DEPTH];
@@ -322,25 +322,27 @@ struct BlockSet {
         // keeps the wait counts exact.
 #pragma unroll
         for (int d = 0; d < DEPTH; ++d) {
-            // (STRAIGHT: a missing chunk re-reads the set's last unit, whose columns are real ones, because it will be
-            // computed and ignored; only a panel with no unit of this granularity at all falls back to the header)
-            const bool have = STRAIGHT ? nu > 0u : (uint32_t)d < n;
+            const bool have = (uint32_t)d < n;
             load_unit<G, DB, VW>(c, have ? bd_off : 0u, have ? bv_off : 0u, have ? unit_of(c, d) : 0u, have ? nu : 1u, buf[d]);
+        }
+    }
+    // The chunks requested in the prologue are computed (run_first, every set in turn) before any set issues a
+    // further load, so that every path to each of these computations has the same loads in flight.  Otherwise, where
+    // paths with different loads in flight meet (a refill under a condition, a loop and its tail), the compiler takes
+    // the stricter wait, and the wait for one set's data turns into a wait for younger loads of other sets as well: a
+    // block chunk then waits for the residual chunk's whole round trip instead of being computed under it.
+    __device__ __forceinline__ void run_first(const Ctx &c)
+    {
+        if constexpr (STRAIGHT) {
+#pragma unroll
+            for (int d = 0; d < DEPTH; ++d)
+                if ((uint32_t)d < n) compute_unit<G, DB, NB, VW>(c, utab, unit_of(c, d), nu, buf[d]);
         }
     }
     __device__ __forceinline__ void run(const Ctx &c)
     {
         uint32_t i = 0;
         if constexpr (STRAIGHT) {
-            // The first DEPTH chunks in code without a branch that depends on how many chunks this wavefront has (a unit
-            // index past the end is computed on the last unit's data and stores nothing).  Loads of another set have
-            // been issued since the prologue (the residual set's, after the first barrier); where paths with different
-            // loads in flight meet, the compiler's wait for this set's data turns into a wait for those younger loads
-            // as well, and the first block chunk then waits for the residual chunk's whole round trip.
-            if (nu > 0u) {
-#pragma unroll
-                for (int d = 0; d < DEPTH; ++d) compute_unit<G, DB, NB, VW>(c, utab, unit_of(c, d), nu, buf[d]);
-            }
             if (n <= (uint32_t)DEPTH) return;
 #pragma unroll
             for (int d = 0; d < DEPTH; ++d)
@@ -661,12 +663,11 @@ __global__ __launch_bounds__(1024) void ecspmv_kernel(const uint32_t count, cons
     // earlier, but those wavefronts request their chunks later, and when the chunks are requested is what decides.)
     // buffers per set: deeper where chunks are small and frequent, shallower where registers run out
     constexpr bool wide = (TM & 12) != 0;
-    BlockSet<16, DB, 1, NB, VW> b16;
-    BlockSet<8, DB, 1, NB, VW> b8;
-    BlockSet<4, DB, wide ? 1 : D4, NB, VW> b4;
-    // (one block set in a launch of its own: its first chunks are computed while the residual set, requested after
-    // the first barrier, is still on its way)
-    BlockSet<2, DB, wide ? 2 : D2, NB, VW, TM == 1 && !BATCH && NB == 1 && VW == 2> b2;
+    constexpr bool straight = !BATCH && NB == 1;
+    BlockSet<16, DB, 1, NB, VW, straight> b16;
+    BlockSet<8, DB, 1, NB, VW, straight> b8;
+    BlockSet<4, DB, wide ? 1 : D4, NB, VW, straight> b4;
+    BlockSet<2, DB, wide ? 2 : D2, NB, VW, straight> b2;
     ResidualSet<DB, wide ? 2 : (TM == 0 && BATCH ? DR0B : DR), TM == 0 && BATCH, NB, VW> rs;
     // A lone launch of an image with one block set requests the residual set's first chunks only after the barrier:
     // a wavefront cannot pass the barrier before its requests are out, and with both sets requested up front the
@@ -767,6 +768,10 @@ __global__ __launch_bounds__(1024) void ecspmv_kernel(const uint32_t count, cons
     ECS_STAMP(c, 4);            // first barrier passed
 
     if constexpr (residual_late) rs.prologue(c, hdr, dealt);
+    if constexpr ((TM & 8) != 0) b16.run_first(c);
+    if constexpr ((TM & 4) != 0) b8.run_first(c);
+    if constexpr ((TM & 2) != 0) b4.run_first(c);
+    if constexpr ((TM & 1) != 0) b2.run_first(c);
     if constexpr ((TM & 8) != 0) b16.run(c);
     if constexpr ((TM & 4) != 0) b8.run(c);
     if constexpr ((TM & 2) != 0) b4.run(c);
