@@ -669,11 +669,13 @@ __global__ __launch_bounds__(1024) void ecspmv_kernel(const uint32_t count, cons
     BlockSet<4, DB, wide ? 1 : D4, NB, VW, straight> b4;
     BlockSet<2, DB, wide ? 2 : D2, NB, VW, straight> b2;
     ResidualSet<DB, wide ? 2 : (TM == 0 && BATCH ? DR0B : DR), TM == 0 && BATCH, NB, VW> rs;
-    // A lone launch of an image with one block set requests the residual set's first chunks only after the barrier:
-    // a wavefront cannot pass the barrier before its requests are out, and with both sets requested up front the
-    // whole panel is on its way before anything is computed (measured: 3-5 % of a lone launch; with more sets, or
-    // with other workgroups sharing the compute unit, requesting everything first is the faster order).
-    constexpr bool residual_late = TM == 1 && !BATCH && NB == 1 && VW == 2;
+    // A launch of an image with block sets that shares its compute units with few others requests the residual set's
+    // first chunks only after the barrier: a wavefront cannot pass the barrier before its requests are out, with every
+    // set requested up front the whole panel is on its way before anything is computed, and the block sets' first
+    // chunks are computed while the residual chunk travels (run_first).  Measured: 3-5 % of a lone launch with one
+    // block set, 2 % of a step (7 % of a 5120 x 5120 launch) with two, 6 % with three; with many workgroups per
+    // compute unit (MODE 2) requesting everything first is the faster order.
+    constexpr bool residual_late = TM != 0 && !BATCH && NB == 1 && VW == 2;
     const uint4 *p4 = reinterpret_cast<const uint4 *>(panel);
     const uint32_t nmeta = meta_stride / 16u;
     const uint32_t nvec = n / 8u;
