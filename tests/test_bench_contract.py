@@ -47,5 +47,6 @@ def test_bench_line_on_the_small_config():
     cb = d["cpu_baseline"]
     assert cb["kind"] == "oracle" and cb["value"] > 0 and cb["cores"] >= 1 and cb["sample"]
     assert d["parity_checked"]["all_ok"] is True and len(d["parity_checked"]["legs"]) >= 3
+    assert d["paper_context"]["speedup_over_best_fp16_baseline"]["max"] == 6.44 and "RTX" in d["paper_context"]["hardware"]
     fl = d["launch_floor"]
     assert 0.5 < fl["empty_launch_256x1024_us"] < 50.0 and fl["step_of_lone_launches_us"] > 0
