@@ -177,7 +177,7 @@ int ecspmv_device_bytes(const ecspmv_matrix *A, size_t *bytes);
  * The authoritative description, with every offset, is the format header that ships with the library's sources. */
 int ecspmv_export_image(const ecspmv_matrix *A, void *host_dst, size_t bytes);
 
-/* Library plumbing, no passage of the paper (the paper's format generation is "once at deployment", Section 8.1).
+/* Library plumbing, no passage of the paper (which builds the format once, ahead of inference: Section 8.1).
  * Copy the image into d_buf (device, 256-byte aligned, >= ecspmv_device_bytes, allocated and owned by the
  * caller) on `stream`, and remember d_buf in the handle.  Returns after the copy has completed. */
 int ecspmv_upload(ecspmv_matrix *A, void *d_buf, size_t bytes, void *stream);
